@@ -1,0 +1,176 @@
+/*
+ * ctcbs -- batched joint CTC/attention beam-search step on one MI355X (gfx950).
+ *
+ * C ABI of the decoding hot path of arXiv 2101.05600 ("Fast offline Transformer-based
+ * end-to-end ASR for real-world applications"): Algorithm 2 (multiple-utterance batched
+ * beam search) with Eq. (1)-(3) as its scoring function, the time-restricted prefix score
+ * of Eq. (5), and the end-of-speech detection of Eq. (4) / Algorithm 3.  The acoustic
+ * encoder and the attention decoder are outside: their outputs (CTC log-posteriors once
+ * per batch, attention log-probabilities once per step) are inputs.
+ *
+ * Symbols: U utterances, Wb beam width, V output ids (blank and eos included), T_i frames
+ * of utterance i, l the 1-based decoding step.  All scores are natural-log probabilities;
+ * "log0" is reported as any value below -1e29 (canonically -1e30).
+ *
+ * Pointers named d_* are DEVICE pointers, h_* are HOST pointers.  The library never takes
+ * ownership of a caller's buffer.  Every call returns 0 on success, a negative CTCBS_E*
+ * code on failure (nothing is thrown, nothing aborts) and ctcbs_step may return the
+ * positive CTCBS_DONE.  All device work is enqueued on the stream given at creation; the
+ * only host synchronisations are inside ctcbs_create (end), ctcbs_finalize,
+ * ctcbs_poll/ctcbs_peek/ctcbs_stats and the optional periodic poll of ctcbs_step.
+ * A handle is not thread-safe.
+ */
+#ifndef CTCBS_H
+#define CTCBS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ctcbs ctcbs_t; /* opaque, owned by the library */
+
+enum {
+  CTCBS_OK = 0,
+  CTCBS_DONE = 1,     /* every utterance of the batch has finished                       */
+  CTCBS_EINVAL = -1,  /* bad argument or unsupported size (see limits below)             */
+  CTCBS_ENOMEM = -2,  /* device or host allocation failed                                */
+  CTCBS_EHIP = -3,    /* a HIP runtime call failed; ctcbs_last_hip_error() has the code  */
+  CTCBS_ESTATE = -4,  /* call not valid in the handle's state                            */
+  CTCBS_ECAP = -5     /* caller's output capacity too small                              */
+};
+
+/* end_flags bits */
+enum {
+  CTCBS_END_BASELINE = 1,  /* Eq. (4): the last M lengths' best ended hypotheses all lie more
+                              than |D_end| below the best ended hypothesis                 */
+  CTCBS_END_TAU_COUNT = 2, /* Algorithm 3: more than C ended hypotheses whose start-time
+                              index tau equals T_i                                         */
+  CTCBS_END_EOS_RUN = 4    /* not in the paper: stop a hypothesis g when, on each of the last
+                              eos_run frames t, phi_t(g) exceeds the running prefix score of
+                              every candidate extension; applies only if those frames lie in
+                              both g's stored range and the current window                 */
+};
+
+/*
+ * Search configuration (Algorithm 2's inputs plus the constants of Sec. 3.2).
+ * Limits: 1 <= beam <= 32; 3 <= vocab; with 0 < cand_k < vocab-2 the vocabulary must not
+ * exceed 12288 ids; 1 <= t_max <= 6140; end_m <= 8; eos_run <= 32.
+ */
+typedef struct {
+  int32_t n_utt;        /* U                                                               */
+  int32_t t_max;        /* frame pitch of d_ctc_logp (>= every T_i)                        */
+  int32_t vocab;        /* V                                                               */
+  int32_t beam;         /* Wb, the paper's B                                               */
+  int32_t blank_id;     /* CTC blank                                                       */
+  int32_t eos_id;       /* <eos>; also the start symbol of Algorithm 2                     */
+  int32_t cand_k;       /* CTC-score only the cand_k ids with the largest attention
+                           log-prob (blank and eos never count; equal values: smaller id);
+                           0 or >= V-2: score all V-2 ids                                  */
+  int32_t win_m1;       /* M1 of s = max(tau - M1, l, 1);        < 0: s = l                */
+  int32_t win_m2;       /* M2 of e = min(tau~ + M2, T_i);        < 0: e = T_i              */
+  float ctc_weight;     /* lambda of Eq. (1)                                               */
+  float length_bonus;   /* added once per label (eos included) to the joint score          */
+  float max_len_ratio;  /* step cap: min(T_i, floor(ratio*T_i) if ratio > 0,               */
+  int32_t max_len_abs;  /*           max_len_abs if > 0), at least 1.  At the cap every
+                           live hypothesis is ended and the utterance finishes.            */
+  int32_t end_flags;    /* CTCBS_END_* bits                                                */
+  int32_t end_m;        /* M of Eq. (4) (paper: 3)                                         */
+  float end_d;          /* log-domain D_end of Eq. (4) (paper: -10)                        */
+  int32_t end_c;        /* C of Algorithm 3 (paper: 2)                                     */
+  int32_t eos_run;      /* frames of the CTCBS_END_EOS_RUN rule (10)                       */
+  int32_t poll_every;   /* > 0: every that many steps ctcbs_step synchronises and reads the
+                           count of finished utterances; 0: never                          */
+  void* stream;         /* hipStream_t; NULL = the null stream                             */
+} ctcbs_config_t;
+
+/*
+ * Views of one step's results.  Device arrays are owned by the library and stay valid
+ * (stream-ordered) until the next ctcbs_step or ctcbs_destroy on the handle.
+ */
+typedef struct {
+  int32_t step;             /* l of the step just enqueued                                 */
+  int32_t n_finished;       /* finished utterances if this call polled, else -1            */
+  const int32_t* d_parent;  /* [U][Wb] old beam slot each new hypothesis extends (GatherB)  */
+  const int32_t* d_token;   /* [U][Wb] label appended                                      */
+  const float* d_score;     /* [U][Wb] joint score, Eq. (1) (+ length bonus)               */
+  const uint8_t* d_live;    /* [U][Wb] 1 = slot holds a hypothesis                         */
+  const uint8_t* d_finished;/* [U]     1 = utterance finished at or before this step       */
+  const int32_t* d_tau;     /* [U][Wb] start-time index tau of the new hypothesis          */
+  const int32_t* d_tau_end; /* [U][Wb] end-time index tau~                                 */
+  const uint8_t* d_eos_added; /* [U][Wb] by OLD slot: g.<eos> entered the ended set        */
+  const uint8_t* d_stopped;   /* [U][Wb] by OLD slot: stopped by the eos-run rule          */
+} ctcbs_step_out_t;
+
+/*
+ * Algorithm 2, initialisation: take the batch's CTC log-posteriors
+ * d_ctc_logp[u][t][k] = log p^c(z_{t+1} = k | h_u), t < h_lens[u] (device, fp32, row pitch
+ * vocab, utterance pitch t_max*vocab; frames at and beyond h_lens[u] are never read), and
+ * set every utterance's beam to the single empty hypothesis.  The posteriors are copied
+ * (token-major) before the call returns, so the caller may release d_ctc_logp afterwards.
+ * On failure *out is NULL.
+ */
+int ctcbs_create(const ctcbs_config_t* cfg, const float* d_ctc_logp, const int32_t* h_lens,
+                 ctcbs_t** out);
+
+/*
+ * One iteration of Algorithm 2's loop (Score_Fn with Eq. (1)-(3)/(5), eos split-off, TopB,
+ * GatherB, the "p > best_score" test, ENDDETECT) for all utterances.
+ * d_att_logp[u][j][k] = log p^a(y^l = k | hypothesis in beam slot j of utterance u) (device,
+ * fp32, [U][Wb][V]); rows of dead slots and finished utterances are not read.  At the first
+ * step only slot 0 of each utterance is live.  The buffer must stay valid until the step's
+ * work has run on the stream.  `out` may be NULL.
+ * Returns CTCBS_DONE (and enqueues nothing) once the handle knows that all utterances are
+ * finished: after a poll saw it, or when the step index passes every utterance's cap.
+ */
+int ctcbs_step(ctcbs_t* h, const float* d_att_logp, ctcbs_step_out_t* out);
+
+/* Synchronise and read how many utterances have finished (Algorithm 2's loop exit test). */
+int ctcbs_poll(ctcbs_t* h, int32_t* n_finished);
+
+/*
+ * Algorithm 2, last line: per utterance the best hypothesis of its ended set (ties: the
+ * one added first).  h_tokens[u*cap ..] receives its labels without the start symbol and
+ * without <eos>, h_ntok[u] their count, h_score[u] its joint score; h_frames (optional,
+ * may be NULL, same layout as h_tokens) receives each label's start-time index tau.
+ * h_flags (optional) gets bit 0 set if the ended set was empty and the best live hypothesis
+ * was returned instead.  May be called at any time; synchronises the stream.
+ */
+int ctcbs_finalize(ctcbs_t* h, int32_t* h_tokens, int32_t cap, int32_t* h_ntok, float* h_score,
+                   int32_t* h_frames, int32_t* h_flags);
+
+/*
+ * Work counters: *cells = sum over steps and live (utterance, beam) groups of
+ * K * (e - s + 1), the number of (utt, beam, candidate, frame) prefix-score terms the
+ * method defines; *steps = steps enqueued so far.  Synchronises.
+ */
+int ctcbs_stats(ctcbs_t* h, uint64_t* cells, int32_t* steps);
+
+/*
+ * Inspection of internal arrays of the last step (tests and debugging; synchronises).
+ * Copies min(bytes, size of the array) bytes to the host buffer and returns the array's
+ * full size in *need (may be NULL).
+ */
+enum {
+  CTCBS_PEEK_CAND_ID = 1,    /* int32  [U][Wb][K] candidate ids, ascending per group        */
+  CTCBS_PEEK_CAND_CTC = 2,   /* double [U][Wb][K] log psi(g.c), Eq. (3)/(5)                 */
+  CTCBS_PEEK_CAND_JOINT = 3, /* double [U][Wb][K] joint score of g.c                        */
+  CTCBS_PEEK_WIN_S = 4,      /* int32  [U][Wb] window start s                               */
+  CTCBS_PEEK_WIN_E = 5,      /* int32  [U][Wb] window end e (e < s: empty)                  */
+  CTCBS_PEEK_CTC_EOS = 6,    /* double [U][Wb] log phi_T(g)                                 */
+  CTCBS_PEEK_JOINT_EOS = 7,  /* double [U][Wb] joint score of g.<eos>                       */
+  CTCBS_PEEK_N_CAND = 8      /* int32  [1] K, candidates per group                          */
+};
+int ctcbs_peek(ctcbs_t* h, int32_t what, void* h_dst, size_t bytes, size_t* need);
+
+void ctcbs_destroy(ctcbs_t* h);
+
+const char* ctcbs_strerror(int code);
+int ctcbs_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CTCBS_H */

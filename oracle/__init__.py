@@ -80,7 +80,7 @@ def lib():
             getattr(L, name).argtypes = [vp]
         L.orc_ended_get.argtypes = [vp, i32, vp, vp, vp, vp]
         L.orc_hyp_get.argtypes = [vp, i32] + [vp] * 9
-        for name in ("orc_hyp_labels", "orc_hyp_gn", "orc_hyp_gb"):
+        for name in ("orc_hyp_labels", "orc_hyp_gn", "orc_hyp_gb", "orc_ended_labels"):
             getattr(L, name).restype = vp
             getattr(L, name).argtypes = [vp, i32]
         L.orc_prefix_and_full.restype = i32
@@ -289,7 +289,10 @@ class OracleUtt:
             s = ctypes.c_double()
             self.L.orc_ended_get(self.h, i, ctypes.addressof(a), ctypes.addressof(b),
                                  ctypes.addressof(c), ctypes.addressof(s))
-            out.append(dict(len=a.value, tau=b.value, slot=c.value, score=s.value))
+            n = a.value - 1
+            lab = _view(self.L.orc_ended_labels(self.h, i), np.int32, n).copy() if n > 0 else \
+                np.empty(0, np.int32)
+            out.append(dict(len=a.value, tau=b.value, slot=c.value, score=s.value, labels=lab))
         return out
 
     def result(self):

@@ -500,6 +500,7 @@ int orc_n_ended(const orc_utt* u) { return u->n_ended; }
 void orc_ended_get(const orc_utt* u, int i, int32_t* len, int32_t* tau, int32_t* slot, double* score) {
   *len = u->ended[i].len; *tau = u->ended[i].tau; *slot = u->ended[i].slot; *score = u->ended[i].score;
 }
+const int32_t* orc_ended_labels(const orc_utt* u, int i) { return u->ended[i].labels; }
 /* hypothesis j of the current beam */
 void orc_hyp_get(const orc_utt* u, int j, int32_t* live, int32_t* len, int32_t* tau, int32_t* tau_end,
                  int32_t* rs, int32_t* re, double* att, double* ctc, double* joint) {

@@ -1,0 +1,210 @@
+"""Python binding of libctcbs (batched joint CTC/attention beam-search step, MI355X).
+
+Argument marshalling only: every step of the decoding path runs in the HIP kernels behind
+the C ABI declared in ``include/ctcbs.h``.  The functions carry the C names.  Device
+buffers are passed as torch tensors (their ``data_ptr()`` is handed over) or raw integer
+addresses.  There is no CPU fallback: if the library is missing, loading raises.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_ROOT = os.path.dirname(_HERE)
+_SO = os.path.join(_HERE, "libctcbs.so")
+_lib = None
+
+OK, DONE, EINVAL, ENOMEM, EHIP, ESTATE, ECAP = 0, 1, -1, -2, -3, -4, -5
+END_BASELINE, END_TAU_COUNT, END_EOS_RUN = 1, 2, 4
+PEEK_CAND_ID, PEEK_CAND_CTC, PEEK_CAND_JOINT, PEEK_WIN_S, PEEK_WIN_E = 1, 2, 3, 4, 5
+PEEK_CTC_EOS, PEEK_JOINT_EOS, PEEK_N_CAND = 6, 7, 8
+
+HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+EXPORTS = ["ctcbs_create", "ctcbs_step", "ctcbs_poll", "ctcbs_finalize", "ctcbs_stats", "ctcbs_peek",
+           "ctcbs_destroy", "ctcbs_strerror", "ctcbs_last_hip_error"]
+
+
+def build():
+    """Compile the HIP library for gfx950 (cross-compiles without a GPU)."""
+    src = os.path.join(_HERE, "csrc", "ctcbs.hip")
+    subprocess.check_call(["hipcc", *HIP_FLAGS, "-o", _SO, src])
+
+
+class Config(ctypes.Structure):
+    _fields_ = [("n_utt", ctypes.c_int32), ("t_max", ctypes.c_int32), ("vocab", ctypes.c_int32),
+                ("beam", ctypes.c_int32), ("blank_id", ctypes.c_int32), ("eos_id", ctypes.c_int32),
+                ("cand_k", ctypes.c_int32), ("win_m1", ctypes.c_int32), ("win_m2", ctypes.c_int32),
+                ("ctc_weight", ctypes.c_float), ("length_bonus", ctypes.c_float),
+                ("max_len_ratio", ctypes.c_float), ("max_len_abs", ctypes.c_int32),
+                ("end_flags", ctypes.c_int32), ("end_m", ctypes.c_int32), ("end_d", ctypes.c_float),
+                ("end_c", ctypes.c_int32), ("eos_run", ctypes.c_int32), ("poll_every", ctypes.c_int32),
+                ("stream", ctypes.c_void_p)]
+
+
+class StepOut(ctypes.Structure):
+    _fields_ = [("step", ctypes.c_int32), ("n_finished", ctypes.c_int32),
+                ("d_parent", ctypes.c_void_p), ("d_token", ctypes.c_void_p),
+                ("d_score", ctypes.c_void_p), ("d_live", ctypes.c_void_p),
+                ("d_finished", ctypes.c_void_p), ("d_tau", ctypes.c_void_p),
+                ("d_tau_end", ctypes.c_void_p), ("d_eos_added", ctypes.c_void_p),
+                ("d_stopped", ctypes.c_void_p)]
+
+
+def lib():
+    """The loaded C library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_SO):
+            raise RuntimeError(f"{_SO} is missing: run __graft_entry__.build() first "
+                               "(there is no CPU fallback)")
+        L = ctypes.CDLL(_SO)
+        vp, i32 = ctypes.c_void_p, ctypes.c_int32
+        L.ctcbs_create.restype = i32
+        L.ctcbs_create.argtypes = [ctypes.POINTER(Config), vp, vp, ctypes.POINTER(vp)]
+        L.ctcbs_step.restype = i32
+        L.ctcbs_step.argtypes = [vp, vp, ctypes.POINTER(StepOut)]
+        L.ctcbs_poll.restype = i32
+        L.ctcbs_poll.argtypes = [vp, ctypes.POINTER(i32)]
+        L.ctcbs_finalize.restype = i32
+        L.ctcbs_finalize.argtypes = [vp, vp, i32, vp, vp, vp, vp]
+        L.ctcbs_stats.restype = i32
+        L.ctcbs_stats.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(i32)]
+        L.ctcbs_peek.restype = i32
+        L.ctcbs_peek.argtypes = [vp, i32, vp, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]
+        L.ctcbs_destroy.restype = None
+        L.ctcbs_destroy.argtypes = [vp]
+        L.ctcbs_strerror.restype = ctypes.c_char_p
+        L.ctcbs_strerror.argtypes = [i32]
+        L.ctcbs_last_hip_error.restype = i32
+        _lib = L
+    return _lib
+
+
+class CtcbsError(RuntimeError):
+    def __init__(self, code):
+        self.code = code
+        msg = lib().ctcbs_strerror(code).decode()
+        if code == EHIP:
+            msg += f" (hip error {lib().ctcbs_last_hip_error()})"
+        super().__init__(f"ctcbs: {msg} [{code}]")
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def make_config(n_utt, t_max, vocab, beam, blank_id=0, eos_id=None, cand_k=0, win_m1=-1, win_m2=-1,
+                ctc_weight=0.3, length_bonus=0.0, max_len_ratio=0.0, max_len_abs=0, end_flags=3,
+                end_m=3, end_d=-10.0, end_c=2, eos_run=10, poll_every=0, stream=None, **_ignored):
+    c = Config()
+    c.n_utt, c.t_max, c.vocab, c.beam, c.blank_id = n_utt, t_max, vocab, beam, blank_id
+    c.eos_id = vocab - 1 if eos_id is None else eos_id
+    c.cand_k, c.win_m1, c.win_m2 = cand_k, win_m1, win_m2
+    c.ctc_weight, c.length_bonus = ctc_weight, length_bonus
+    c.max_len_ratio, c.max_len_abs = max_len_ratio, max_len_abs
+    c.end_flags, c.end_m, c.end_d, c.end_c, c.eos_run = end_flags, end_m, end_d, end_c, eos_run
+    c.poll_every = poll_every
+    c.stream = stream
+    return c
+
+
+def ctcbs_create(cfg: Config, d_ctc_logp, h_lens):
+    """-> opaque handle (int).  d_ctc_logp: device fp32 [U][t_max][V]; h_lens: host int32 [U]."""
+    lens = np.ascontiguousarray(h_lens, dtype=np.int32)
+    out = ctypes.c_void_p()
+    rc = lib().ctcbs_create(ctypes.byref(cfg), _ptr(d_ctc_logp), lens.ctypes.data_as(ctypes.c_void_p),
+                            ctypes.byref(out))
+    if rc != OK:
+        raise CtcbsError(rc)
+    return out.value
+
+
+def ctcbs_step(handle, d_att_logp, out: StepOut = None):
+    """-> OK or DONE.  d_att_logp: device fp32 [U][Wb][V]."""
+    rc = lib().ctcbs_step(handle, _ptr(d_att_logp), ctypes.byref(out) if out is not None else None)
+    if rc < 0:
+        raise CtcbsError(rc)
+    return rc
+
+
+def ctcbs_poll(handle):
+    n = ctypes.c_int32()
+    rc = lib().ctcbs_poll(handle, ctypes.byref(n))
+    if rc != OK:
+        raise CtcbsError(rc)
+    return n.value
+
+
+def ctcbs_finalize(handle, n_utt, cap, want_frames=False):
+    """-> (tokens [U][cap] int32, ntok [U], score [U] fp32, frames or None, flags [U])."""
+    tok = np.full((n_utt, max(cap, 1)), -1, dtype=np.int32)
+    frm = np.full((n_utt, max(cap, 1)), -1, dtype=np.int32) if want_frames else None
+    nt = np.zeros(n_utt, dtype=np.int32)
+    sc = np.zeros(n_utt, dtype=np.float32)
+    fl = np.zeros(n_utt, dtype=np.int32)
+    vp = ctypes.c_void_p
+    rc = lib().ctcbs_finalize(handle, tok.ctypes.data_as(vp), cap, nt.ctypes.data_as(vp),
+                              sc.ctypes.data_as(vp), frm.ctypes.data_as(vp) if want_frames else None,
+                              fl.ctypes.data_as(vp))
+    if rc != OK:
+        raise CtcbsError(rc)
+    return tok, nt, sc, frm, fl
+
+
+def ctcbs_stats(handle):
+    c, s = ctypes.c_uint64(), ctypes.c_int32()
+    rc = lib().ctcbs_stats(handle, ctypes.byref(c), ctypes.byref(s))
+    if rc != OK:
+        raise CtcbsError(rc)
+    return c.value, s.value
+
+
+_PEEK_DTYPE = {PEEK_CAND_ID: np.int32, PEEK_CAND_CTC: np.float64, PEEK_CAND_JOINT: np.float64,
+               PEEK_WIN_S: np.int32, PEEK_WIN_E: np.int32, PEEK_CTC_EOS: np.float64,
+               PEEK_JOINT_EOS: np.float64, PEEK_N_CAND: np.int32}
+
+
+def ctcbs_peek(handle, what):
+    need = ctypes.c_size_t()
+    rc = lib().ctcbs_peek(handle, what, None, 0, ctypes.byref(need))
+    if rc != OK:
+        raise CtcbsError(rc)
+    dt = np.dtype(_PEEK_DTYPE[what])
+    out = np.empty(need.value // dt.itemsize, dtype=dt)
+    rc = lib().ctcbs_peek(handle, what, out.ctypes.data_as(ctypes.c_void_p), need.value, None)
+    if rc != OK:
+        raise CtcbsError(rc)
+    return out
+
+
+def ctcbs_destroy(handle):
+    if handle:
+        lib().ctcbs_destroy(handle)
+
+
+def ctcbs_strerror(code):
+    return lib().ctcbs_strerror(code).decode()
+
+
+def view(ptr, shape, dtype):
+    """A torch tensor aliasing a library-owned device array (step outputs)."""
+    import torch
+    n = int(np.prod(shape))
+    tdt = {np.int32: torch.int32, np.float32: torch.float32, np.uint8: torch.uint8}[dtype]
+    nbytes = n * np.dtype(dtype).itemsize
+
+    class _Holder:
+        pass
+
+    hold = _Holder()
+    hold.__cuda_array_interface__ = {
+        "shape": (nbytes,), "typestr": "|u1", "data": (int(ptr), False), "version": 2}
+    return torch.as_tensor(hold, device="cuda").view(tdt).reshape(shape)

@@ -1,0 +1,156 @@
+// Shared device-side definitions of the ctcbs kernels (gfx950, wave64).
+//
+// Numeric form.  Every hypothesis g keeps its two CTC forward variables (paths ending in
+// its last label / ending in blank; their log-sum is the paper's phi_t(g) of Eq. (3)) as
+// fp32 values RELATIVE to an fp64 offset off(g) = log psi(g), the hypothesis's own prefix
+// score.  Near the frames that matter the relative values are O(1), so fp32 keeps ~1e-6
+// absolute accuracy no matter how negative the cumulative score has become; cumulative
+// CTC, attention and joint scores are accumulated in fp64, one add per hypothesis and step.
+// log0 is the finite sentinel -1e30 (anything below -1e29 is treated as log0).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define CTCBS_WAVE 64
+#define LOG0F (-1.0e30f)
+#define LOG0_CLASS (-1.0e29f)
+#define LOG0D (-1.0e30)
+#define MAX_BEAM 32
+#define MAX_END_M 8
+#define MAX_EOS_RUN 32
+#define RADIX_BINS 4096
+
+struct UttState {            // per utterance, touched by one thread of the select kernel
+  double best_score;         // best joint score in the ended set
+  double ring_score[MAX_END_M];  // best ended score per length, lengths l, l-1, ... (ring by l % M)
+  double fb_score;
+  int32_t ring_tag[MAX_END_M];
+  int32_t n_ended, best_step, best_slot, cnt_tau_T;
+  int32_t finished_step;     // 0 while running
+  int32_t pad;
+};
+
+struct Params {
+  // sizes and configuration
+  int32_t U, V, Wb, K, Tp, t_max, blank_id, eos_id;
+  int32_t restricted;        // 1: top-K attention candidates; 0: every id but blank/eos
+  int32_t win_m1, win_m2, end_flags, end_m, end_c, eos_run, l_cap;
+  float end_d;
+  double lambda, beta;
+  // posteriors, token-major: xT[(u*V + k)*Tp + t] = log p^c(z_t = k), t = 1..T_u; 0 elsewhere
+  float* xT;
+  const int32_t* lens;       // [U]
+  const int32_t* lmax;       // [U] step cap per utterance
+  // hypothesis state, two buffers (index b): forward variables [b][U][Wb][Tp] (relative) and
+  // per-hypothesis records [b][U][Wb]
+  float* gn[2];
+  float* gb[2];
+  int32_t* h_live[2];
+  int32_t* h_last[2];
+  int32_t* h_rs[2];
+  int32_t* h_re[2];
+  int32_t* h_tau[2];
+  int32_t* h_tau_end[2];
+  double* h_off[2];          // log psi(g): cumulative CTC prefix score
+  double* h_att[2];          // cumulative attention log-prob, Eq. (2)
+  double* h_joint[2];        // joint score of the hypothesis
+  // per-step scratch between the score and the select kernel
+  int32_t* win_s;            // [U][Wb]
+  int32_t* win_e;
+  int32_t* cand_id;          // [U][Wb][K]
+  float* cand_inc;           // [U][Wb][K] log psi(g.c) - off(g)
+  float* cand_att;           // [U][Wb][K] this step's attention log-prob of c
+  float* cand_pre;           // [U][Wb][K] scratch of the eos-run rule
+  double* cand_ctc;          // [U][Wb][K] log psi(g.c)
+  double* cand_joint;        // [U][Wb][K]
+  int32_t* grp_n;            // [U][Wb] entries of the group's sorted list
+  int32_t* grp_idx;          // [U][Wb][Wb] candidate indices, best first
+  double* ctc_eos;           // [U][Wb]
+  double* joint_eos;         // [U][Wb]
+  int32_t* stopped;          // [U][Wb] eos-run rule fired
+  long long* grp_cells;      // [U][Wb]
+  // utterance state
+  UttState* utt;             // [U]
+  uint8_t* finished;         // [U]
+  unsigned long long* cells; // [U]
+  int32_t* n_finished;       // [1]
+  // back-pointer trie, level l holds the hypotheses of length l: [l_cap+1][U][Wb]
+  int32_t* trie_parent;
+  int32_t* trie_token;
+  int32_t* trie_tau;
+  // step outputs
+  int32_t* out_parent;
+  int32_t* out_token;
+  float* out_score;
+  uint8_t* out_live;
+  int32_t* out_tau;
+  int32_t* out_tau_end;
+  uint8_t* out_eos_added;
+  uint8_t* out_stopped;
+};
+
+__device__ __forceinline__ float lae(float a, float b) {
+  // log(e^a + e^b); with both operands at the log0 sentinel the result stays in the log0 class
+  float m = fmaxf(a, b);
+  float d = -fabsf(a - b);
+  return m + __logf(1.0f + __expf(d));
+}
+
+__device__ __forceinline__ float canon0(float v) { return v < LOG0_CLASS ? LOG0F : v; }
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v, int lane) {
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    uint32_t t = __shfl_up(v, o);
+    if (lane >= o) v += t;
+  }
+  return v;
+}
+
+// Exclusive prefix sum of one uint32 per thread over the block; *total = block sum.
+// scratch: one uint32 per wave (+1).  Contains two barriers.
+template <int BLOCK>
+__device__ __forceinline__ uint32_t block_excl_scan_u32(uint32_t v, uint32_t* scratch, uint32_t* total) {
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  constexpr int NW = BLOCK / 64;
+  uint32_t inc = wave_incl_scan_u32(v, lane);
+  __syncthreads();                    // scratch may still be read from a previous use
+  if (lane == 63) scratch[w] = inc;
+  __syncthreads();
+  uint32_t base = 0, tot = 0;
+#pragma unroll
+  for (int i = 0; i < NW; ++i) {
+    uint32_t s = scratch[i];
+    if (i < w) base += s;
+    tot += s;
+  }
+  *total = tot;
+  return base + inc - v;
+}
+
+// Order-preserving map of an attention log-prob to uint32 (larger value -> larger key).
+// Excluded ids get key 0, NaN gets key 1: both sort below every number, -inf included.
+__device__ __forceinline__ uint32_t att_key(float v, int id, int blank_id, int eos_id) {
+  if (id == blank_id || id == eos_id) return 0u;
+  if (v != v) return 1u;
+  uint32_t u = __float_as_uint(v);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// k-th candidate id when every id except blank and eos is a candidate (ascending ids).
+__device__ __forceinline__ int full_v_id(int i, int lo_ex, int hi_ex) {
+  int id = i;
+  if (id >= lo_ex) ++id;
+  if (id >= hi_ex) ++id;
+  return id;
+}

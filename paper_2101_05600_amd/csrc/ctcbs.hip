@@ -1,0 +1,339 @@
+// Host side of the ctcbs C ABI (see include/ctcbs.h): argument checks, device memory,
+// kernel launches.  Every step of the decoding path runs in the kernels of k_*.h.
+#include "../../include/ctcbs.h"
+
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <new>
+#include <stdlib.h>
+#include <string.h>
+#include <vector>
+
+#include "common.h"
+#include "k_finalize.h"
+#include "k_ingest.h"
+#include "k_score.h"
+#include "k_select.h"
+
+static thread_local int g_last_hip = 0;
+
+#define HIPCHK(expr)                                   \
+  do {                                                 \
+    hipError_t _e = (expr);                            \
+    if (_e != hipSuccess) { g_last_hip = (int)_e; return CTCBS_EHIP; } \
+  } while (0)
+
+struct ctcbs {
+  ctcbs_config_t cfg;
+  Params p;
+  ScoreSmem sm;
+  hipStream_t stream;
+  std::vector<void*> allocs;
+  std::vector<int32_t> lens, lmax;
+  int32_t step;        // steps enqueued
+  int32_t cur;         // buffer holding the current beam
+  int32_t l_cap;       // largest step cap over the batch
+  int32_t known_finished;
+  size_t score_smem_bytes;
+  int score_block, score_lpc, select_block;
+  // result staging
+  int32_t *d_tokens, *d_frames, *d_ntok, *d_flags;
+  float* d_score;
+  int32_t res_cap;
+};
+
+template <typename T>
+static int dev_alloc(ctcbs* h, T** out, size_t n) {
+  void* ptr = nullptr;
+  size_t bytes = n * sizeof(T);
+  if (bytes == 0) bytes = sizeof(T);
+  hipError_t e = hipMalloc(&ptr, bytes);
+  if (e != hipSuccess) { g_last_hip = (int)e; (void)hipGetLastError(); return CTCBS_ENOMEM; }
+  h->allocs.push_back(ptr);
+  *out = (T*)ptr;
+  return CTCBS_OK;
+}
+
+static void free_all(ctcbs* h) {
+  for (void* q : h->allocs) (void)hipFree(q);
+  h->allocs.clear();
+}
+
+static int step_cap(const ctcbs_config_t* c, int T) {
+  int l = T;
+  if (c->max_len_ratio > 0.0f) { int r = (int)floor((double)c->max_len_ratio * (double)T); if (r < l) l = r; }
+  if (c->max_len_abs > 0 && c->max_len_abs < l) l = c->max_len_abs;
+  if (l < 1) l = 1;
+  return l;
+}
+
+extern "C" const char* ctcbs_strerror(int code) {
+  switch (code) {
+    case CTCBS_OK: return "ok";
+    case CTCBS_DONE: return "all utterances finished";
+    case CTCBS_EINVAL: return "invalid argument or unsupported size";
+    case CTCBS_ENOMEM: return "out of memory";
+    case CTCBS_EHIP: return "HIP runtime error";
+    case CTCBS_ESTATE: return "call not valid in this state";
+    case CTCBS_ECAP: return "output capacity too small";
+    default: return "unknown ctcbs error code";
+  }
+}
+
+extern "C" int ctcbs_last_hip_error(void) { return g_last_hip; }
+
+static int validate(const ctcbs_config_t* c) {
+  if (c->n_utt < 1 || c->t_max < 1 || c->t_max > 6140 || c->vocab < 3) return CTCBS_EINVAL;
+  if (c->beam < 1 || c->beam > MAX_BEAM) return CTCBS_EINVAL;
+  if (c->blank_id < 0 || c->blank_id >= c->vocab || c->eos_id < 0 || c->eos_id >= c->vocab ||
+      c->blank_id == c->eos_id) return CTCBS_EINVAL;
+  if (c->cand_k < 0) return CTCBS_EINVAL;
+  bool restricted = c->cand_k > 0 && c->cand_k < c->vocab - 2;
+  if (restricted && c->vocab > 12288) return CTCBS_EINVAL;
+  if (!(c->ctc_weight >= 0.0f && c->ctc_weight <= 1.0f)) return CTCBS_EINVAL;
+  if (c->length_bonus != c->length_bonus || c->max_len_ratio != c->max_len_ratio || c->max_len_ratio < 0.0f)
+    return CTCBS_EINVAL;
+  if (c->max_len_abs < 0) return CTCBS_EINVAL;
+  if (c->end_flags & ~7) return CTCBS_EINVAL;
+  if ((c->end_flags & CTCBS_END_BASELINE) && (c->end_m < 1 || c->end_m > MAX_END_M)) return CTCBS_EINVAL;
+  if ((c->end_flags & CTCBS_END_TAU_COUNT) && c->end_c < 0) return CTCBS_EINVAL;
+  if ((c->end_flags & CTCBS_END_EOS_RUN) && (c->eos_run < 1 || c->eos_run > MAX_EOS_RUN)) return CTCBS_EINVAL;
+  if (c->poll_every < 0) return CTCBS_EINVAL;
+  if ((long long)c->n_utt * c->beam > (1ll << 24)) return CTCBS_EINVAL;
+  return CTCBS_OK;
+}
+
+static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens) {
+  const ctcbs_config_t& c = h->cfg;
+  Params& p = h->p;
+  memset(&p, 0, sizeof p);
+  const int U = c.n_utt, V = c.vocab, Wb = c.beam;
+  const bool restricted = c.cand_k > 0 && c.cand_k < V - 2;
+  const int K = restricted ? c.cand_k : V - 2;
+  p.U = U; p.V = V; p.Wb = Wb; p.K = K;
+  p.Tp = ((c.t_max + 1 + 3) / 4) * 4 + 4;       // frames 0..t_max plus slack for aligned float4 reads
+  p.t_max = c.t_max; p.blank_id = c.blank_id; p.eos_id = c.eos_id; p.restricted = restricted ? 1 : 0;
+  p.win_m1 = c.win_m1; p.win_m2 = c.win_m2; p.end_flags = c.end_flags;
+  p.end_m = (c.end_m >= 1 && c.end_m <= MAX_END_M) ? c.end_m : 1;
+  p.end_c = c.end_c; p.eos_run = c.eos_run; p.end_d = c.end_d;
+  p.lambda = (double)c.ctc_weight; p.beta = (double)c.length_bonus;
+
+  h->lens.assign(h_lens, h_lens + U);
+  h->lmax.resize(U);
+  h->l_cap = 1;
+  for (int u = 0; u < U; ++u) {
+    if (h->lens[u] < 1 || h->lens[u] > c.t_max) return CTCBS_EINVAL;
+    h->lmax[u] = step_cap(&c, h->lens[u]);
+    if (h->lmax[u] > h->l_cap) h->l_cap = h->lmax[u];
+  }
+  p.l_cap = h->l_cap;
+
+  const size_t UW = (size_t)U * Wb;
+  int rc;
+  int32_t *d_lens, *d_lmax;
+#define A(ptr, n) if ((rc = dev_alloc(h, &(ptr), (n))) != CTCBS_OK) return rc
+  A(p.xT, (size_t)U * V * p.Tp);
+  A(d_lens, (size_t)U); A(d_lmax, (size_t)U);
+  p.lens = d_lens; p.lmax = d_lmax;
+  for (int b = 0; b < 2; ++b) {
+    A(p.gn[b], UW * p.Tp); A(p.gb[b], UW * p.Tp);
+    A(p.h_live[b], UW); A(p.h_last[b], UW); A(p.h_rs[b], UW); A(p.h_re[b], UW);
+    A(p.h_tau[b], UW); A(p.h_tau_end[b], UW);
+    A(p.h_off[b], UW); A(p.h_att[b], UW); A(p.h_joint[b], UW);
+  }
+  A(p.win_s, UW); A(p.win_e, UW);
+  A(p.cand_id, UW * K); A(p.cand_inc, UW * K); A(p.cand_att, UW * K); A(p.cand_pre, UW * K);
+  A(p.cand_ctc, UW * K); A(p.cand_joint, UW * K);
+  A(p.grp_n, UW); A(p.grp_idx, UW * Wb);
+  A(p.ctc_eos, UW); A(p.joint_eos, UW); A(p.stopped, UW); A(p.grp_cells, UW);
+  A(p.utt, (size_t)U); A(p.finished, (size_t)U); A(p.cells, (size_t)U); A(p.n_finished, (size_t)1);
+  const size_t trie_n = (size_t)(h->l_cap + 1) * UW;
+  A(p.trie_parent, trie_n); A(p.trie_token, trie_n); A(p.trie_tau, trie_n);
+  A(p.out_parent, UW); A(p.out_token, UW); A(p.out_score, UW); A(p.out_live, UW);
+  A(p.out_tau, UW); A(p.out_tau_end, UW); A(p.out_eos_added, UW); A(p.out_stopped, UW);
+  h->res_cap = h->l_cap;
+  A(h->d_tokens, (size_t)U * h->res_cap); A(h->d_frames, (size_t)U * h->res_cap);
+  A(h->d_ntok, (size_t)U); A(h->d_flags, (size_t)U); A(h->d_score, (size_t)U);
+#undef A
+
+  hipStream_t st = h->stream;
+  HIPCHK(hipMemcpyAsync(d_lens, h->lens.data(), sizeof(int32_t) * U, hipMemcpyHostToDevice, st));
+  HIPCHK(hipMemcpyAsync(d_lmax, h->lmax.data(), sizeof(int32_t) * U, hipMemcpyHostToDevice, st));
+  HIPCHK(hipMemsetAsync(p.xT, 0, sizeof(float) * (size_t)U * V * p.Tp, st));
+  HIPCHK(hipMemsetAsync(p.grp_n, 0, sizeof(int32_t) * UW, st));
+  HIPCHK(hipMemsetAsync(p.stopped, 0, sizeof(int32_t) * UW, st));
+
+  dim3 tg((V + 63) / 64, (c.t_max + 63) / 64, U);
+  hipLaunchKernelGGL(k_transpose, tg, dim3(256), 0, st, p, d_ctc_logp);
+  HIPCHK(hipGetLastError());
+  hipLaunchKernelGGL(k_init_state, dim3(U), dim3(64), 0, st, p);
+  HIPCHK(hipGetLastError());
+
+  // launch shapes of the per-step kernels
+  h->score_block = 256;
+  const bool windowed = c.win_m1 >= 0 && c.win_m2 >= 0 && (c.win_m1 + c.win_m2) <= 448;
+  h->score_lpc = windowed ? 16 : 64;
+  ScoreSmem& sm = h->sm;
+  size_t off = 0;
+  sm.off_att = (int32_t)off; off += restricted ? (((size_t)V * 4 + 15) & ~(size_t)15) : 0;
+  sm.off_work = (int32_t)off;
+  size_t work = (size_t)2 * p.Tp * 4;
+  if (restricted && work < (size_t)RADIX_BINS * 4) work = (size_t)RADIX_BINS * 4;
+  off += (work + 15) & ~(size_t)15;
+  sm.off_small = (int32_t)off;
+  if (K <= h->score_block) off += (((size_t)K * 4 + 7) & ~(size_t)7) + (size_t)K * 8;
+  sm.wp_max = p.Tp;
+  h->score_smem_bytes = off;
+  if (off > 160 * 1024) return CTCBS_EINVAL;
+  int nw = Wb < 16 ? Wb : 16;
+  h->select_block = 64 * (nw <= 4 ? 4 : (nw <= 8 ? 8 : 16));
+
+  h->step = 0; h->cur = 0; h->known_finished = 0;
+  HIPCHK(hipStreamSynchronize(st));
+  return CTCBS_OK;
+}
+
+extern "C" int ctcbs_create(const ctcbs_config_t* cfg, const float* d_ctc_logp, const int32_t* h_lens,
+                            ctcbs_t** out) {
+  if (out) *out = nullptr;
+  if (!cfg || !d_ctc_logp || !h_lens || !out) return CTCBS_EINVAL;
+  int rc = validate(cfg);
+  if (rc != CTCBS_OK) return rc;
+  ctcbs* h = new (std::nothrow) ctcbs();
+  if (!h) return CTCBS_ENOMEM;
+  h->cfg = *cfg;
+  h->stream = (hipStream_t)cfg->stream;
+  rc = create_impl(h, d_ctc_logp, h_lens);
+  if (rc != CTCBS_OK) { free_all(h); delete h; return rc; }
+  *out = h;
+  return CTCBS_OK;
+}
+
+template <int BLOCK, int LPC>
+static hipError_t launch_score(ctcbs* h, const float* att, int l) {
+  if (h->score_smem_bytes > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute((const void*)k_score<BLOCK, LPC>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->score_smem_bytes);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((k_score<BLOCK, LPC>), dim3(h->p.U * h->p.Wb), dim3(BLOCK), h->score_smem_bytes,
+                     h->stream, h->p, h->sm, att, l, h->cur);
+  return hipGetLastError();
+}
+
+extern "C" int ctcbs_step(ctcbs_t* h, const float* d_att_logp, ctcbs_step_out_t* out) {
+  if (!h || !d_att_logp) return CTCBS_EINVAL;
+  if (h->known_finished >= h->p.U || h->step >= h->l_cap) return CTCBS_DONE;
+  const int l = h->step + 1;
+  hipError_t e = (h->score_lpc == 16) ? launch_score<256, 16>(h, d_att_logp, l)
+                                       : launch_score<256, 64>(h, d_att_logp, l);
+  HIPCHK(e);
+  if (h->p.K > h->score_block) {
+    hipLaunchKernelGGL((k_group_top<256>), dim3(h->p.U * h->p.Wb), dim3(256), 0, h->stream, h->p, h->cur);
+    HIPCHK(hipGetLastError());
+  }
+  switch (h->select_block) {
+    case 256: hipLaunchKernelGGL((k_select<256>), dim3(h->p.U), dim3(256), 0, h->stream, h->p, l, h->cur); break;
+    case 512: hipLaunchKernelGGL((k_select<512>), dim3(h->p.U), dim3(512), 0, h->stream, h->p, l, h->cur); break;
+    default: hipLaunchKernelGGL((k_select<1024>), dim3(h->p.U), dim3(1024), 0, h->stream, h->p, l, h->cur); break;
+  }
+  HIPCHK(hipGetLastError());
+  h->step = l;
+  h->cur ^= 1;
+  int polled = -1;
+  if (h->cfg.poll_every > 0 && (l % h->cfg.poll_every) == 0) {
+    int rc = ctcbs_poll(h, &polled);
+    if (rc != CTCBS_OK) return rc;
+  }
+  if (out) {
+    const Params& p = h->p;
+    out->step = l; out->n_finished = polled;
+    out->d_parent = p.out_parent; out->d_token = p.out_token; out->d_score = p.out_score;
+    out->d_live = p.out_live; out->d_finished = p.finished; out->d_tau = p.out_tau;
+    out->d_tau_end = p.out_tau_end; out->d_eos_added = p.out_eos_added; out->d_stopped = p.out_stopped;
+  }
+  return CTCBS_OK;
+}
+
+extern "C" int ctcbs_poll(ctcbs_t* h, int32_t* n_finished) {
+  if (!h) return CTCBS_EINVAL;
+  int32_t v = 0;
+  HIPCHK(hipMemcpyAsync(&v, h->p.n_finished, sizeof v, hipMemcpyDeviceToHost, h->stream));
+  HIPCHK(hipStreamSynchronize(h->stream));
+  h->known_finished = v;
+  if (n_finished) *n_finished = v;
+  return CTCBS_OK;
+}
+
+extern "C" int ctcbs_finalize(ctcbs_t* h, int32_t* h_tokens, int32_t cap, int32_t* h_ntok, float* h_score,
+                              int32_t* h_frames, int32_t* h_flags) {
+  if (!h || !h_tokens || !h_ntok || !h_score || cap < 0) return CTCBS_EINVAL;
+  const int U = h->p.U, rc_cap = h->res_cap;
+  hipLaunchKernelGGL(k_finalize, dim3((U + 63) / 64), dim3(64), 0, h->stream, h->p, h->cur, h->step, rc_cap,
+                     h->d_tokens, h->d_frames, h->d_ntok, h->d_score, h->d_flags);
+  HIPCHK(hipGetLastError());
+  std::vector<int32_t> tok((size_t)U * rc_cap), frm((size_t)U * rc_cap), nt(U), fl(U);
+  HIPCHK(hipMemcpyAsync(tok.data(), h->d_tokens, tok.size() * 4, hipMemcpyDeviceToHost, h->stream));
+  HIPCHK(hipMemcpyAsync(frm.data(), h->d_frames, frm.size() * 4, hipMemcpyDeviceToHost, h->stream));
+  HIPCHK(hipMemcpyAsync(nt.data(), h->d_ntok, (size_t)U * 4, hipMemcpyDeviceToHost, h->stream));
+  HIPCHK(hipMemcpyAsync(fl.data(), h->d_flags, (size_t)U * 4, hipMemcpyDeviceToHost, h->stream));
+  HIPCHK(hipMemcpyAsync(h_score, h->d_score, (size_t)U * 4, hipMemcpyDeviceToHost, h->stream));
+  HIPCHK(hipStreamSynchronize(h->stream));
+  for (int u = 0; u < U; ++u) {
+    if (nt[u] < 0 || nt[u] > cap) return CTCBS_ECAP;
+    h_ntok[u] = nt[u];
+    for (int k = 0; k < nt[u]; ++k) {
+      h_tokens[(size_t)u * cap + k] = tok[(size_t)u * rc_cap + k];
+      if (h_frames) h_frames[(size_t)u * cap + k] = frm[(size_t)u * rc_cap + k];
+    }
+    if (h_flags) h_flags[u] = fl[u];
+  }
+  return CTCBS_OK;
+}
+
+extern "C" int ctcbs_stats(ctcbs_t* h, uint64_t* cells, int32_t* steps) {
+  if (!h) return CTCBS_EINVAL;
+  std::vector<unsigned long long> c(h->p.U);
+  HIPCHK(hipMemcpyAsync(c.data(), h->p.cells, c.size() * 8, hipMemcpyDeviceToHost, h->stream));
+  HIPCHK(hipStreamSynchronize(h->stream));
+  unsigned long long tot = 0;
+  for (auto v : c) tot += v;
+  if (cells) *cells = tot;
+  if (steps) *steps = h->step;
+  return CTCBS_OK;
+}
+
+extern "C" int ctcbs_peek(ctcbs_t* h, int32_t what, void* h_dst, size_t bytes, size_t* need) {
+  if (!h) return CTCBS_EINVAL;
+  const Params& p = h->p;
+  const size_t UW = (size_t)p.U * p.Wb;
+  const void* src = nullptr; size_t sz = 0;
+  int32_t k = p.K;
+  switch (what) {
+    case CTCBS_PEEK_CAND_ID: src = p.cand_id; sz = UW * p.K * 4; break;
+    case CTCBS_PEEK_CAND_CTC: src = p.cand_ctc; sz = UW * p.K * 8; break;
+    case CTCBS_PEEK_CAND_JOINT: src = p.cand_joint; sz = UW * p.K * 8; break;
+    case CTCBS_PEEK_WIN_S: src = p.win_s; sz = UW * 4; break;
+    case CTCBS_PEEK_WIN_E: src = p.win_e; sz = UW * 4; break;
+    case CTCBS_PEEK_CTC_EOS: src = p.ctc_eos; sz = UW * 8; break;
+    case CTCBS_PEEK_JOINT_EOS: src = p.joint_eos; sz = UW * 8; break;
+    case CTCBS_PEEK_N_CAND:
+      if (need) *need = 4;
+      if (h_dst && bytes >= 4) memcpy(h_dst, &k, 4);
+      return CTCBS_OK;
+    default: return CTCBS_EINVAL;
+  }
+  if (need) *need = sz;
+  if (h_dst && bytes) {
+    HIPCHK(hipMemcpyAsync(h_dst, src, bytes < sz ? bytes : sz, hipMemcpyDeviceToHost, h->stream));
+    HIPCHK(hipStreamSynchronize(h->stream));
+  }
+  return CTCBS_OK;
+}
+
+extern "C" void ctcbs_destroy(ctcbs_t* h) {
+  if (!h) return;
+  (void)hipStreamSynchronize(h->stream);
+  free_all(h);
+  delete h;
+}

@@ -1,0 +1,223 @@
+"""GPU parity: libctcbs (through its C ABI) against the CPU oracle, step by step.
+
+Tolerances (written out here): integer results (candidate ids, windows, selected parent/token,
+time indices, flags, final labels) must be identical wherever the oracle's deciding margin
+exceeds 1e-4; fused scores and CTC prefix scores within 1e-4 absolute (fp32 path, fp64 oracle).
+"""
+import numpy as np
+import pytest
+
+import gen
+import oracle
+from helpers import GpuDecoder, lockstep_decode, orc_cfg_from, host_att
+
+pytestmark = pytest.mark.gpu
+
+
+def small(name="cfg1", **over):
+    w = gen.workload(name)
+    w.update(over)
+    w["eos_id"] = w["vocab"] - 1
+    return w
+
+
+def make_inputs(w, pad=np.nan):
+    lens = gen.workload_lengths(w)
+    return lens, gen.workload_ctc(w, lens, pad_value=pad)
+
+
+def test_cfg0_full_vocabulary_single_utterance():
+    w = gen.workload("cfg0")
+    lens, ctc = make_inputs(w)
+    rep, res = lockstep_decode(w, ctc, lens)
+    print(rep, res["ntok"], res["score"])
+    assert rep["utt_steps"] >= 5 and rep["max_score_err"] < 1e-4
+    assert res["cells"] == int(res["oracle_cells"])
+
+
+@pytest.mark.parametrize("variant", ["topk", "topk_window_e2", "fullv_window", "beam1", "wide_beam"])
+def test_small_batches_ragged(variant):
+    base = dict(n_utt=5, t_lo=37, t_hi=211, vocab=700, beam=6, cand_k=24, win_m1=-1, win_m2=-1,
+                end_flags=3)
+    if variant == "topk_window_e2":
+        base.update(win_m1=12, win_m2=17, end_flags=7, eos_run=6)
+    elif variant == "fullv_window":
+        base.update(vocab=90, cand_k=0, win_m1=9, win_m2=30, end_flags=7, beam=5)
+    elif variant == "beam1":
+        base.update(beam=1, cand_k=300, vocab=421, end_flags=7, win_m1=25, win_m2=25)  # K > block size
+    elif variant == "wide_beam":
+        base.update(beam=17, cand_k=9, n_utt=3, win_m1=30, win_m2=30, end_flags=7)
+    w = small("cfg1", **base)
+    lens, ctc = make_inputs(w)
+    rep, res = lockstep_decode(w, ctc, lens)
+    print(variant, rep)
+    assert rep["max_score_err"] < 1e-4 and rep["max_ctc_err"] < 1e-4
+    assert res["cells"] == int(res["oracle_cells"])
+    assert rep["exact_sel_steps"] >= 0.9 * rep["utt_steps"]
+
+
+def test_cfg1_shape_all_utterances():
+    w = gen.workload("cfg1")
+    lens, ctc = make_inputs(w)
+    rep, res = lockstep_decode(w, ctc, lens, peek=True, check_utts=[0, 3, 7, 12], max_steps=None)
+    print(rep)
+    assert rep["max_score_err"] < 1e-4 and rep["max_ctc_err"] < 1e-4
+
+
+def test_batch_independence_and_padding_never_read():
+    """An utterance decoded alone equals the same utterance inside a batch (padding NaN-poisoned)."""
+    w = small("cfg1", n_utt=4, t_lo=50, t_hi=160, vocab=300, beam=4, cand_k=16, win_m1=15, win_m2=15,
+              end_flags=7, eos_run=5)
+    lens, ctc = make_inputs(w, pad=np.nan)
+
+    def free_run(ctc_b, lens_b, utt_rows):
+        dec = GpuDecoder(w, ctc_b, lens_b)
+        U, Wb = len(lens_b), w["beam"]
+        basis = gen.prefix_hash([])
+        hashes = [[basis] * Wb for _ in range(U)]
+        live = np.zeros((U, Wb), bool); live[:, 0] = True
+        step = 0
+        trace = []
+        while True:
+            step += 1
+            # attention rows are keyed by the utterance's id in the full batch
+            att = np.full((U, Wb, w["vocab"]), np.nan, np.float32)
+            for i, u in enumerate(utt_rows):
+                for j in range(Wb):
+                    if live[i, j]:
+                        att[i, j] = gen.att_row(w["seed"], u, step, hashes[i][j], w["vocab"])
+            if dec.step(att) == dec.m.DONE:
+                break
+            out = dec.outputs()
+            trace.append({k: v.copy() for k, v in out.items()})
+            nh = [[basis] * Wb for _ in range(U)]
+            for i in range(U):
+                for n in range(Wb):
+                    if out["live"][i, n]:
+                        nh[i][n] = gen.prefix_hash_extend(hashes[i][out["parent"][i, n]], out["token"][i, n])
+            hashes, live = nh, out["live"].astype(bool)
+            if out["finished"].all():
+                break
+        r = dec.finalize(frames=True)
+        dec.close()
+        return trace, r
+
+    tr_all, (tok, nt, sc, frm, fl) = free_run(ctc, lens, [0, 1, 2, 3])
+    for u in (1, 3):
+        t1 = int(lens[u])
+        tr_one, (tok1, nt1, sc1, frm1, fl1) = free_run(ctc[u:u + 1, :t1], lens[u:u + 1], [u])
+        assert nt1[0] == nt[u] and np.array_equal(tok1[0, :nt1[0]], tok[u, :nt[u]])
+        assert sc1[0] == sc[u] and np.array_equal(frm1[0, :nt1[0]], frm[u, :nt[u]])
+        for a, b in zip(tr_one, tr_all):
+            for k in ("parent", "token", "score", "tau", "tau_end"):
+                assert np.array_equal(a[k][0], b[k][u]), k
+    # reversed batch order gives the same hypotheses
+    tr_rev, (tokr, ntr, scr, _, _) = free_run(ctc[::-1].copy(), lens[::-1].copy(), [3, 2, 1, 0])
+    for u in range(4):
+        assert ntr[3 - u] == nt[u] and np.array_equal(tokr[3 - u, :nt[u]], tok[u, :nt[u]]) and scr[3 - u] == sc[u]
+
+
+def test_constructed_eos_run_stop_and_time_stamps():
+    """Sharply peaked posteriors with a blank tail: the eos-run rule stops the finished transcript,
+    and the per-label frames returned by finalize are the emitting frames."""
+    T, V = 50, 6
+    x = np.full((T, V), 0.02 / (V - 1), np.float64)
+    emits = {6: 1, 15: 2, 27: 3}
+    for t in range(1, T + 1):
+        x[t - 1, emits.get(t, 0)] = 0.98
+    x = np.log(x).astype(np.float32)[None]
+    w = small("cfg0", n_utt=1, vocab=V, beam=1, cand_k=0, ctc_weight=0.5, max_len_abs=20, end_flags=4,
+              eos_run=10, t_lo=T, t_hi=T)
+    dec = GpuDecoder(w, x, [T])
+    stopped_at = None
+    for step, want in enumerate([1, 2, 3, 4, 4, 4], start=1):
+        att = np.full((1, 1, V), -4.0, np.float32)
+        att[0, 0, want] = -0.1
+        att[0, 0, V - 1] = -9.0
+        if dec.step(att) == dec.m.DONE:
+            break
+        out = dec.outputs()
+        if out["stopped"][0, 0] and stopped_at is None:
+            stopped_at = step
+        if out["finished"][0]:
+            break
+    tok, nt, sc, frm, fl = dec.finalize(frames=True)
+    dec.close()
+    assert stopped_at == 4 and nt[0] == 3 and tok[0, :3].tolist() == [1, 2, 3]
+    assert frm[0, :3].tolist() == [6, 15, 27] and fl[0] == 0
+
+
+def test_stats_poll_and_done():
+    w = small("cfg1", n_utt=3, t_lo=30, t_hi=60, vocab=200, beam=3, cand_k=8)
+    lens, ctc = make_inputs(w)
+    dec = GpuDecoder(w, ctc, lens, poll_every=2)
+    m = dec.m
+    att = np.zeros((3, 3, 200), np.float32)
+    rng = np.random.default_rng(0)
+    n = 0
+    while True:
+        att[:] = rng.normal(size=att.shape).astype(np.float32)
+        rc = dec.step(att)
+        if rc == m.DONE:
+            break
+        n += 1
+        assert dec.out.step == n
+        if n % 2 == 0:
+            assert dec.out.n_finished == int(dec.outputs()["finished"].sum())
+        else:
+            assert dec.out.n_finished == -1
+        assert n <= 20
+    assert m.ctcbs_poll(dec.h) == 3
+    cells, steps = m.ctcbs_stats(dec.h)
+    assert steps == n and cells > 0
+    assert dec.step(att) == m.DONE          # stays done, enqueues nothing
+    assert m.ctcbs_stats(dec.h)[1] == n
+    dec.close()
+
+
+def test_abi_rejects_bad_arguments():
+    import ctypes
+    import torch
+    import paper_2101_05600_amd as m
+    L = m.lib()
+    good = dict(n_utt=2, t_max=20, vocab=50, beam=3, cand_k=5)
+    x = torch.zeros((2, 20, 50), device="cuda")
+    lens = np.array([20, 11], np.int32)
+
+    def create(**over):
+        kw = dict(good); kw.update(over)
+        out = ctypes.c_void_p(123)
+        rc = L.ctcbs_create(ctypes.byref(m.make_config(**kw)), x.data_ptr(),
+                            lens.ctypes.data_as(ctypes.c_void_p), ctypes.byref(out))
+        return rc, out.value
+
+    for bad in (dict(n_utt=0), dict(beam=0), dict(beam=33), dict(vocab=2), dict(blank_id=50),
+                dict(eos_id=0), dict(cand_k=-1), dict(ctc_weight=1.5), dict(t_max=7000),
+                dict(end_flags=8), dict(end_m=9), dict(eos_run=0, end_flags=4),
+                dict(vocab=20000, cand_k=5), dict(max_len_ratio=-1.0)):
+        rc, h = create(**bad)
+        assert rc == m.EINVAL and h is None, bad
+    out = ctypes.c_void_p()
+    cfg = m.make_config(**good)
+    assert L.ctcbs_create(None, x.data_ptr(), lens.ctypes.data_as(ctypes.c_void_p), ctypes.byref(out)) == m.EINVAL
+    assert L.ctcbs_create(ctypes.byref(cfg), None, lens.ctypes.data_as(ctypes.c_void_p), ctypes.byref(out)) == m.EINVAL
+    bad_lens = np.array([21, 5], np.int32)
+    assert L.ctcbs_create(ctypes.byref(cfg), x.data_ptr(), bad_lens.ctypes.data_as(ctypes.c_void_p),
+                          ctypes.byref(out)) == m.EINVAL
+    rc, h = create()
+    assert rc == m.OK and h
+    assert L.ctcbs_step(h, None, None) == m.EINVAL
+    assert L.ctcbs_step(None, x.data_ptr(), None) == m.EINVAL
+    tok = np.zeros((2, 1), np.int32); nt = np.zeros(2, np.int32); sc = np.zeros(2, np.float32)
+    vp = ctypes.c_void_p
+    att = torch.randn((2, 3, 50), device="cuda")
+    att[:, :, 49] = -1.0e4                  # eos never attractive: nothing enters the ended set
+    for _ in range(4):
+        assert L.ctcbs_step(h, att.data_ptr(), None) == m.OK
+    # capacity too small for a 4-label hypothesis (nothing has ended: best live hypothesis is returned)
+    assert L.ctcbs_finalize(h, tok.ctypes.data_as(vp), 1, nt.ctypes.data_as(vp), sc.ctypes.data_as(vp),
+                            None, None) == m.ECAP
+    assert L.ctcbs_peek(h, 99, None, 0, None) == m.EINVAL
+    assert m.ctcbs_strerror(m.ECAP) and m.ctcbs_strerror(-77)
+    L.ctcbs_destroy(h)
+    L.ctcbs_destroy(None)
