@@ -137,7 +137,7 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
       uint32_t k = att_key(s_att[i], i, p.blank_id, p.eos_id);
       bool take = (k > prefix) || (k == prefix && eq_before < krem);
       if (k == prefix) ++eq_before;
-      if (take) {
+      if (take && pos < (uint32_t)K) {
         if (smallk) s_cid[pos] = i;
         g_cid[pos] = i;
         ++pos;
