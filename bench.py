@@ -1,0 +1,256 @@
+#!/usr/bin/env python3
+"""Throughput of the batched joint CTC/attention beam-search path on one MI355X.
+
+One benchmark "step" is one whole decode of one batch: ctcbs_create (ingest of the CTC
+posteriors) -> ctcbs_step until every utterance has finished -> ctcbs_finalize.  All inputs
+are synthetic and already resident in HBM when the timed region starts: the CTC
+log-posteriors come from the device generator, and the attention rows of every step are
+recorded once, in an untimed decode with the same generator keyed by the hypotheses'
+prefixes, and replayed from HBM in the timed decodes (decoding is deterministic, so every
+timed decode takes the recorded path; this is checked).
+
+Prints ONE JSON line (see the design doc for the fields).
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--poll-every", type=int, default=8)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=24, help="utterances in the oracle's timed sample")
+    return ap.parse_args()
+
+
+class Batch:
+    """Device-resident synthetic batch plus the recorded attention rows of its decode."""
+
+    def __init__(self, w, poll_every):
+        import torch
+        import gen
+        import paper_2101_05600_amd as m
+        self.torch, self.gen, self.m, self.w = torch, gen, m, w
+        self.U, self.Wb, self.V = w["n_utt"], w["beam"], w["vocab"]
+        self.lens = gen.workload_lengths(w)
+        self.t_max = int(self.lens.max())
+        self.poll_every = poll_every
+        self.stream = torch.cuda.current_stream().cuda_stream
+        self.d_lens = torch.from_numpy(self.lens).cuda()
+        self.d_ctc = torch.empty((self.U, self.t_max, self.V), dtype=torch.float32, device="cuda")
+        rc = gen.dev().gen_dev_ctc(w["seed"], self.U, self.d_lens.data_ptr(), self.t_max, self.V,
+                                   w["blank_id"], w["blank_boost"], w["p_boost"], w["zipf_s"],
+                                   self.d_ctc.data_ptr(), self.stream)
+        assert rc == 0, f"gen_dev_ctc: hip error {rc}"
+        torch.cuda.synchronize()
+        self.cfg = m.make_config(n_utt=self.U, t_max=self.t_max, poll_every=poll_every,
+                                 stream=self.stream,
+                                 **{k: v for k, v in w.items() if k not in ("n_utt", "stream")})
+        self.l_cap = int(max(self._cap(int(t)) for t in self.lens))
+        self.att = None
+        self.n_steps = 0
+
+    def _cap(self, T):
+        w = self.w
+        l = T
+        if w["max_len_ratio"] > 0:
+            l = min(l, int(np.floor(np.float32(w["max_len_ratio"]).astype(np.float64) * T)))
+        if w["max_len_abs"] > 0:
+            l = min(l, w["max_len_abs"])
+        return max(l, 1)
+
+    def record(self):
+        """Untimed decode that produces (and keeps) every step's attention rows."""
+        torch, m, gen, w = self.torch, self.m, self.gen, self.w
+        U, Wb, V = self.U, self.Wb, self.V
+        self.att = torch.empty((self.l_cap, U, Wb, V), dtype=torch.float32, device="cuda")
+        hashes = [torch.zeros((U, Wb), dtype=torch.int64, device="cuda") for _ in range(2)]
+        h = m.ctcbs_create(self.cfg, self.d_ctc, self.lens)
+        out = m.StepOut()
+        G = gen.dev()
+        step = 0
+        try:
+            while step < self.l_cap:
+                step += 1
+                rc = G.gen_dev_att_step(w["seed"], step, U, Wb, V, w["att_scale"],
+                                        hashes[(step - 1) & 1].data_ptr(),
+                                        out.d_parent if step > 1 else None,
+                                        out.d_token if step > 1 else None,
+                                        out.d_live if step > 1 else None,
+                                        hashes[step & 1].data_ptr(), self.att[step - 1].data_ptr(),
+                                        self.stream)
+                assert rc == 0, f"gen_dev_att_step: hip error {rc}"
+                if m.ctcbs_step(h, self.att[step - 1], out) == m.DONE:
+                    step -= 1
+                    break
+                if out.n_finished == U:
+                    break
+            self.n_steps = step
+            res = m.ctcbs_finalize(h, U, self.l_cap)
+            stats = m.ctcbs_stats(h)
+        finally:
+            m.ctcbs_destroy(h)
+        self.ref = res
+        self.cells, self.groups, _ = stats
+        return res
+
+    def decode(self, profile=False):
+        """One timed-style decode replaying the recorded rows; returns (result, handle stats)."""
+        m, U = self.m, self.U
+        h = m.ctcbs_create(self.cfg, self.d_ctc, self.lens)
+        out = m.StepOut()
+        try:
+            if profile:
+                m.ctcbs_profile(h, True)
+            for step in range(1, self.n_steps + 1):
+                if m.ctcbs_step(h, self.att[step - 1], out) == m.DONE:
+                    break
+                if out.n_finished == U:
+                    break
+            res = m.ctcbs_finalize(h, U, self.l_cap)
+            prof = m.ctcbs_profile_read(h) if profile else None
+        finally:
+            m.ctcbs_destroy(h)
+        return res, prof
+
+
+def cpu_baseline(batch, n_sample):
+    """The oracle, free-running, on the first n_sample utterances of the same batch (their CTC
+    posteriors are the device bytes copied back); only oracle calls are timed."""
+    import gen
+    import oracle
+    w = batch.w
+    n = min(n_sample, batch.U)
+    x = batch.d_ctc[:n].cpu().numpy()
+    kw = {k: w[k] for k in (
+        "vocab", "beam", "blank_id", "eos_id", "cand_k", "win_m1", "win_m2", "ctc_weight",
+        "length_bonus", "max_len_ratio", "max_len_abs", "end_flags", "end_m", "end_d", "end_c",
+        "eos_run")}
+    for k in ("ctc_weight", "length_bonus", "max_len_ratio", "end_d"):
+        kw[k] = float(np.float32(kw[k]))          # the values the fp32 fields of the C ABI carry
+    cfg = oracle.make_cfg(**kw)
+    L = oracle.lib()
+    cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")), n)
+
+    def run(utt_ids, threads):
+        os.environ["OMP_NUM_THREADS"] = str(threads)
+        utts = [oracle.OracleUtt(x[u, :batch.lens[u]], cfg) for u in utt_ids]
+        arr = (ctypes.c_void_p * len(utts))(*[o.h for o in utts])
+        fin = np.zeros(len(utts), np.int32)
+        Wb, V = w["beam"], w["vocab"]
+        basis = gen.prefix_hash([])
+        t_or = 0.0
+        step = 0
+        while not all(o.finished for o in utts):
+            step += 1
+            ids, hs = [], []
+            for i, o in enumerate(utts):
+                for j in range(Wb):
+                    hyp = o.hyp(j) if not o.finished else None
+                    ids.append(utt_ids[i])
+                    hs.append(gen.prefix_hash(hyp["labels"]) if hyp and hyp["live"] else basis)
+            att = gen.att_rows(w["seed"], ids, step, hs, V, w["att_scale"])
+            t0 = time.perf_counter()
+            L.orc_batch_step_auto(arr, len(utts), att.ctypes.data_as(ctypes.c_void_p),
+                                  fin.ctypes.data_as(ctypes.c_void_p))
+            t_or += time.perf_counter() - t0
+        return sum(o.cells for o in utts), t_or, len(utts)
+
+    L.orc_set_threads.argtypes = [ctypes.c_int]
+    L.orc_set_threads(1)
+    c1, t1, n1 = run(list(range(min(3, n))), 1)
+    L.orc_set_threads(cores)
+    cN, tN, nN = run(list(range(n)), cores)
+    return {"value": cN / tN, "unit": "cells/s", "cores": cores, "kind": "oracle",
+            "sample": f"first {nN} of {batch.U} utterances of the same batch, whole decodes, "
+                      f"free-running with host-generated attention rows; oracle calls only "
+                      f"({tN:.2f} s on {cores} threads)",
+            "utterances_per_sec": nN / tN,
+            "single_thread": {"value": c1 / t1, "utterances_per_sec": n1 / t1, "utterances": n1,
+                              "seconds": t1}}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this path runs on ONE GPU (utterances are independent; several GPUs would "
+              "each run their own batches with nothing exchanged) -- use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import gen
+    import paper_2101_05600_amd as m
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    m.lib()
+    w = gen.workload(a.workload)
+    b = Batch(w, a.poll_every)
+    ref = b.record()
+    for _ in range(a.warmup):
+        b.decode()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        res, _ = b.decode()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    for x, y in zip(res[:3], ref[:3]):
+        assert np.array_equal(x, y), "timed decode did not reproduce the recorded decode"
+    ms = dt / a.steps * 1e3
+    # dominant kernel: score kernel, HIP events on its own stream, one extra decode
+    _, prof = b.decode(profile=True)
+    score_ms, select_ms, n_prof = prof
+    K = int(w["cand_k"]) if 0 < w["cand_k"] < w["vocab"] - 2 else w["vocab"] - 2
+    restricted = 0 < w["cand_k"] < w["vocab"] - 2
+    # algorithmic bytes of the score kernel over the decode: candidate columns 4 B per term,
+    # the parent's two forward variables 8 B per window frame, the attention row 4V per group
+    bytes_score = 4.0 * b.cells + 8.0 * b.cells / K + (4.0 * w["vocab"] * b.groups if restricted else 0.0)
+    ach = bytes_score / (score_ms * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"k_score_{a.workload}_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("traffic_bytes_per_launch")
+        except Exception:
+            traffic = None
+    line = {
+        "metric": "CTC prefix-score cells/sec (utt·beam·cand·frame) + utterances/sec at B=64",
+        "value": b.cells / (dt / a.steps), "unit": "cells/s",
+        "utterances_per_sec": b.U / (dt / a.steps),
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{a.workload}: U={b.U} utterances, T in [{int(b.lens.min())},{int(b.lens.max())}], "
+                               f"V={b.V}, beam {b.Wb}, top-{K} candidates, window M1={w['win_m1']} "
+                               f"M2={w['win_m2']}, end_flags={w['end_flags']}; one step = one whole "
+                               f"batch decode (create + {b.n_steps} beam-search steps + finalize)",
+                   "decode_steps": b.n_steps, "cells_per_decode": b.cells,
+                   "poll_every": a.poll_every},
+        "roofline": {"bound": "hbm", "kernel": "k_score", "achieved": ach, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": traffic,
+                     "avg_launch_us": score_ms * 1e3 / max(n_prof, 1),
+                     "algorithmic_bytes_per_launch": bytes_score / max(n_prof, 1),
+                     "select_kernel_avg_us": select_ms * 1e3 / max(n_prof, 1)},
+    }
+    if not a.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(b, a.cpu_sample)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

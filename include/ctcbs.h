@@ -144,9 +144,19 @@ int ctcbs_finalize(ctcbs_t* h, int32_t* h_tokens, int32_t cap, int32_t* h_ntok, 
 /*
  * Work counters: *cells = sum over steps and live (utterance, beam) groups of
  * K * (e - s + 1), the number of (utt, beam, candidate, frame) prefix-score terms the
- * method defines; *steps = steps enqueued so far.  Synchronises.
+ * method defines (Eq. (3)/(5) summands); *groups = live (utterance, beam) groups summed over
+ * steps; *steps = steps enqueued so far.  Any pointer may be NULL.  Synchronises.
  */
-int ctcbs_stats(ctcbs_t* h, uint64_t* cells, int32_t* steps);
+int ctcbs_stats(ctcbs_t* h, uint64_t* cells, uint64_t* groups, int32_t* steps);
+
+/*
+ * Measurement aid.  After ctcbs_profile(h, 1) every ctcbs_step brackets its score kernel
+ * and its select kernel with HIP events on the handle's stream; ctcbs_profile_read
+ * synchronises and returns the summed durations (milliseconds) of the steps recorded since
+ * profiling was enabled, and their count.
+ */
+int ctcbs_profile(ctcbs_t* h, int32_t enable);
+int ctcbs_profile_read(ctcbs_t* h, double* score_ms, double* select_ms, int32_t* n_steps);
 
 /*
  * Inspection of internal arrays of the last step (tests and debugging; synchronises).

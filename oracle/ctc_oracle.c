@@ -36,6 +36,9 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 #define ORC_LOG0 (-1.0e30)
 #define ORC_END_BASELINE 1
@@ -547,6 +550,14 @@ int orc_prefix_and_full(const float* x, int T, int V, int blank_id, const int32_
   *log_phi_T = (g->rs <= T && g->re >= T) ? lae(g->gn[T], g->gb[T]) : -INFINITY;
   hyp_free(&a); hyp_free(&b);
   return 0;
+}
+
+void orc_set_threads(int n) {
+#ifdef _OPENMP
+  omp_set_num_threads(n > 0 ? n : 1);
+#else
+  (void)n;
+#endif
 }
 
 /* Parallel-for over utterances of one free-running step (CPU-baseline timing only). */

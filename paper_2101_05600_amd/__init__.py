@@ -25,7 +25,8 @@ HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 EXPORTS = ["ctcbs_create", "ctcbs_step", "ctcbs_poll", "ctcbs_finalize", "ctcbs_stats", "ctcbs_peek",
-           "ctcbs_destroy", "ctcbs_strerror", "ctcbs_last_hip_error"]
+           "ctcbs_destroy", "ctcbs_strerror", "ctcbs_last_hip_error", "ctcbs_profile",
+           "ctcbs_profile_read"]
 
 
 def build():
@@ -72,7 +73,13 @@ def lib():
         L.ctcbs_finalize.restype = i32
         L.ctcbs_finalize.argtypes = [vp, vp, i32, vp, vp, vp, vp]
         L.ctcbs_stats.restype = i32
-        L.ctcbs_stats.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(i32)]
+        L.ctcbs_stats.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint64),
+                                  ctypes.POINTER(i32)]
+        L.ctcbs_profile.restype = i32
+        L.ctcbs_profile.argtypes = [vp, i32]
+        L.ctcbs_profile_read.restype = i32
+        L.ctcbs_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double),
+                                         ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
         L.ctcbs_peek.restype = i32
         L.ctcbs_peek.argtypes = [vp, i32, vp, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]
         L.ctcbs_destroy.restype = None
@@ -160,11 +167,27 @@ def ctcbs_finalize(handle, n_utt, cap, want_frames=False):
 
 
 def ctcbs_stats(handle):
-    c, s = ctypes.c_uint64(), ctypes.c_int32()
-    rc = lib().ctcbs_stats(handle, ctypes.byref(c), ctypes.byref(s))
+    """-> (cells, groups, steps)"""
+    c, g, s = ctypes.c_uint64(), ctypes.c_uint64(), ctypes.c_int32()
+    rc = lib().ctcbs_stats(handle, ctypes.byref(c), ctypes.byref(g), ctypes.byref(s))
     if rc != OK:
         raise CtcbsError(rc)
-    return c.value, s.value
+    return c.value, g.value, s.value
+
+
+def ctcbs_profile(handle, enable=True):
+    rc = lib().ctcbs_profile(handle, 1 if enable else 0)
+    if rc != OK:
+        raise CtcbsError(rc)
+
+
+def ctcbs_profile_read(handle):
+    """-> (score_ms, select_ms, n_steps)"""
+    a, b, n = ctypes.c_double(), ctypes.c_double(), ctypes.c_int32()
+    rc = lib().ctcbs_profile_read(handle, ctypes.byref(a), ctypes.byref(b), ctypes.byref(n))
+    if rc != OK:
+        raise CtcbsError(rc)
+    return a.value, b.value, n.value
 
 
 _PEEK_DTYPE = {PEEK_CAND_ID: np.int32, PEEK_CAND_CTC: np.float64, PEEK_CAND_JOINT: np.float64,

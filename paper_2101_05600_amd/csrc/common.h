@@ -72,7 +72,8 @@ struct Params {
   // utterance state
   UttState* utt;             // [U]
   uint8_t* finished;         // [U]
-  unsigned long long* cells; // [U]
+  unsigned long long* cells; // [U] prefix-score terms so far
+  unsigned long long* groups;// [U] live (utterance, beam) groups so far
   int32_t* n_finished;       // [1]
   // back-pointer trie, level l holds the hypotheses of length l: [l_cap+1][U][Wb]
   int32_t* trie_parent;

@@ -40,6 +40,10 @@ struct ctcbs {
   int32_t *d_tokens, *d_frames, *d_ntok, *d_flags;
   float* d_score;
   int32_t res_cap;
+  // optional per-kernel timing
+  bool profiling;
+  std::vector<hipEvent_t> events;   // 3 per recorded step: before score, after score, after select
+  size_t ev_used;
 };
 
 template <typename T>
@@ -146,7 +150,8 @@ static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens)
   A(p.cand_ctc, UW * K); A(p.cand_joint, UW * K);
   A(p.grp_n, UW); A(p.grp_idx, UW * Wb);
   A(p.ctc_eos, UW); A(p.joint_eos, UW); A(p.stopped, UW); A(p.grp_cells, UW);
-  A(p.utt, (size_t)U); A(p.finished, (size_t)U); A(p.cells, (size_t)U); A(p.n_finished, (size_t)1);
+  A(p.utt, (size_t)U); A(p.finished, (size_t)U); A(p.cells, (size_t)U); A(p.groups, (size_t)U);
+  A(p.n_finished, (size_t)1);
   const size_t trie_n = (size_t)(h->l_cap + 1) * UW;
   A(p.trie_parent, trie_n); A(p.trie_token, trie_n); A(p.trie_tau, trie_n);
   A(p.out_parent, UW); A(p.out_token, UW); A(p.out_score, UW); A(p.out_live, UW);
@@ -189,6 +194,7 @@ static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens)
   h->select_block = 64 * (nw <= 4 ? 4 : (nw <= 8 ? 8 : 16));
 
   h->step = 0; h->cur = 0; h->known_finished = 0;
+  h->profiling = false; h->ev_used = 0;
   HIPCHK(hipStreamSynchronize(st));
   return CTCBS_OK;
 }
@@ -225,6 +231,12 @@ extern "C" int ctcbs_step(ctcbs_t* h, const float* d_att_logp, ctcbs_step_out_t*
   if (!h || !d_att_logp) return CTCBS_EINVAL;
   if (h->known_finished >= h->p.U || h->step >= h->l_cap) return CTCBS_DONE;
   const int l = h->step + 1;
+  hipEvent_t* ev = nullptr;
+  if (h->profiling && h->ev_used + 3 <= h->events.size()) {
+    ev = &h->events[h->ev_used];
+    h->ev_used += 3;
+    HIPCHK(hipEventRecord(ev[0], h->stream));
+  }
   hipError_t e = (h->score_lpc == 16) ? launch_score<256, 16>(h, d_att_logp, l)
                                        : launch_score<256, 64>(h, d_att_logp, l);
   HIPCHK(e);
@@ -232,12 +244,14 @@ extern "C" int ctcbs_step(ctcbs_t* h, const float* d_att_logp, ctcbs_step_out_t*
     hipLaunchKernelGGL((k_group_top<256>), dim3(h->p.U * h->p.Wb), dim3(256), 0, h->stream, h->p, h->cur);
     HIPCHK(hipGetLastError());
   }
+  if (ev) HIPCHK(hipEventRecord(ev[1], h->stream));
   switch (h->select_block) {
     case 256: hipLaunchKernelGGL((k_select<256>), dim3(h->p.U), dim3(256), 0, h->stream, h->p, l, h->cur); break;
     case 512: hipLaunchKernelGGL((k_select<512>), dim3(h->p.U), dim3(512), 0, h->stream, h->p, l, h->cur); break;
     default: hipLaunchKernelGGL((k_select<1024>), dim3(h->p.U), dim3(1024), 0, h->stream, h->p, l, h->cur); break;
   }
   HIPCHK(hipGetLastError());
+  if (ev) HIPCHK(hipEventRecord(ev[2], h->stream));
   h->step = l;
   h->cur ^= 1;
   int polled = -1;
@@ -291,15 +305,52 @@ extern "C" int ctcbs_finalize(ctcbs_t* h, int32_t* h_tokens, int32_t cap, int32_
   return CTCBS_OK;
 }
 
-extern "C" int ctcbs_stats(ctcbs_t* h, uint64_t* cells, int32_t* steps) {
+extern "C" int ctcbs_stats(ctcbs_t* h, uint64_t* cells, uint64_t* groups, int32_t* steps) {
   if (!h) return CTCBS_EINVAL;
-  std::vector<unsigned long long> c(h->p.U);
+  std::vector<unsigned long long> c(h->p.U), g(h->p.U);
   HIPCHK(hipMemcpyAsync(c.data(), h->p.cells, c.size() * 8, hipMemcpyDeviceToHost, h->stream));
+  HIPCHK(hipMemcpyAsync(g.data(), h->p.groups, g.size() * 8, hipMemcpyDeviceToHost, h->stream));
   HIPCHK(hipStreamSynchronize(h->stream));
-  unsigned long long tot = 0;
+  unsigned long long tot = 0, gt = 0;
   for (auto v : c) tot += v;
+  for (auto v : g) gt += v;
   if (cells) *cells = tot;
+  if (groups) *groups = gt;
   if (steps) *steps = h->step;
+  return CTCBS_OK;
+}
+
+extern "C" int ctcbs_profile(ctcbs_t* h, int32_t enable) {
+  if (!h) return CTCBS_EINVAL;
+  if (enable && h->events.empty()) {
+    h->events.resize((size_t)3 * (h->l_cap + 1));
+    for (size_t i = 0; i < h->events.size(); ++i) {
+      hipError_t e = hipEventCreate(&h->events[i]);
+      if (e != hipSuccess) {
+        for (size_t k = 0; k < i; ++k) (void)hipEventDestroy(h->events[k]);
+        h->events.clear();
+        g_last_hip = (int)e;
+        return CTCBS_EHIP;
+      }
+    }
+  }
+  h->profiling = enable != 0;
+  h->ev_used = 0;
+  return CTCBS_OK;
+}
+
+extern "C" int ctcbs_profile_read(ctcbs_t* h, double* score_ms, double* select_ms, int32_t* n_steps) {
+  if (!h) return CTCBS_EINVAL;
+  HIPCHK(hipStreamSynchronize(h->stream));
+  double a = 0.0, b = 0.0;
+  for (size_t i = 0; i + 3 <= h->ev_used; i += 3) {
+    float ms = 0.0f;
+    HIPCHK(hipEventElapsedTime(&ms, h->events[i], h->events[i + 1])); a += ms;
+    HIPCHK(hipEventElapsedTime(&ms, h->events[i + 1], h->events[i + 2])); b += ms;
+  }
+  if (score_ms) *score_ms = a;
+  if (select_ms) *select_ms = b;
+  if (n_steps) *n_steps = (int32_t)(h->ev_used / 3);
   return CTCBS_OK;
 }
 
@@ -334,6 +385,7 @@ extern "C" int ctcbs_peek(ctcbs_t* h, int32_t what, void* h_dst, size_t bytes, s
 extern "C" void ctcbs_destroy(ctcbs_t* h) {
   if (!h) return;
   (void)hipStreamSynchronize(h->stream);
+  for (hipEvent_t e : h->events) (void)hipEventDestroy(e);
   free_all(h);
   delete h;
 }

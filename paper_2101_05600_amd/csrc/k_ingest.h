@@ -69,6 +69,7 @@ __global__ __launch_bounds__(64) void k_init_state(Params p) {
     p.utt[u] = s;
     p.finished[u] = 0;
     p.cells[u] = 0ull;
+    p.groups[u] = 0ull;
     if (u == 0) *p.n_finished = 0;
   }
 }

@@ -81,12 +81,13 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
     const double best = has_best ? s_J[s_sel[0]] : LOG0D;
     const bool forced = (l >= p.lmax[u]);
     UttState st = p.utt[u];
-    long long cells = 0;
+    long long cells = 0, ngroups = 0;
     for (int j = 0; j < Wb; ++j) {
       const size_t h = h0 + j;
       int added = 0, stp = 0;
       if (p.h_live[cur][h]) {
         cells += p.grp_cells[h];
+        ++ngroups;
         stp = p.stopped[h];
         const double je = p.joint_eos[h];
         const bool je_ok = je > (double)LOG0_CLASS;
@@ -124,6 +125,7 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
     }
     p.utt[u] = st;
     p.cells[u] += (unsigned long long)cells;
+    p.groups[u] += (unsigned long long)ngroups;
     s_nnew = n_new; s_fin = fin ? 1 : 0;
   }
   __syncthreads();

@@ -11,10 +11,14 @@ PEEKS = None
 
 
 def orc_cfg_from(w):
-    return oracle.make_cfg(**{k: w[k] for k in (
+    kw = {k: w[k] for k in (
         "vocab", "beam", "blank_id", "eos_id", "cand_k", "win_m1", "win_m2", "ctc_weight",
         "length_bonus", "max_len_ratio", "max_len_abs", "end_flags", "end_m", "end_d", "end_c",
-        "eos_run")})
+        "eos_run")}
+    # the C ABI carries these three as fp32: give the oracle the same values
+    for k in ("ctc_weight", "length_bonus", "max_len_ratio", "end_d"):
+        kw[k] = float(np.float32(kw[k]))
+    return oracle.make_cfg(**kw)
 
 
 def host_att(w, step, hashes, live, n_utt, dead_fill=np.nan):
@@ -120,7 +124,7 @@ def lockstep_decode(w, ctc, lens, peek=True, check_utts=None, max_steps=None, pr
         tok, nt, sc, frm, fl = dec.finalize()
         if max_steps is None:
             ls.check_results(tok, nt, sc, fl)
-        cells, steps = dec.m.ctcbs_stats(dec.h)
+        cells, _groups, steps = dec.m.ctcbs_stats(dec.h)
         res = dict(tokens=tok, ntok=nt, score=sc, flags=fl, cells=cells, steps=steps,
                    oracle_cells=sum(o.cells for o in ls.utts))
         return ls.report, res

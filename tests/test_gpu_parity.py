@@ -168,10 +168,10 @@ def test_stats_poll_and_done():
             assert dec.out.n_finished == -1
         assert n <= 20
     assert m.ctcbs_poll(dec.h) == 3
-    cells, steps = m.ctcbs_stats(dec.h)
+    cells, groups, steps = m.ctcbs_stats(dec.h)
     assert steps == n and cells > 0
     assert dec.step(att) == m.DONE          # stays done, enqueues nothing
-    assert m.ctcbs_stats(dec.h)[1] == n
+    assert m.ctcbs_stats(dec.h)[2] == n
     dec.close()
 
 
