@@ -64,7 +64,13 @@ struct Params {
   double* cand_ctc;          // [U][Wb][K] log psi(g.c)
   double* cand_joint;        // [U][Wb][K]
   int32_t* grp_n;            // [U][Wb] entries of the group's sorted list
-  int32_t* grp_idx;          // [U][Wb][Wb] candidate indices, best first
+  // the group's best-first list, [U][Wb][Wb]: joint score, candidate index, token,
+  // prefix-score increment, this step's attention log-prob
+  double* grp_J;
+  int32_t* grp_ci;
+  int32_t* grp_tok;
+  float* grp_inc;
+  float* grp_att;
   double* ctc_eos;           // [U][Wb]
   double* joint_eos;         // [U][Wb]
   int32_t* stopped;          // [U][Wb] eos-run rule fired

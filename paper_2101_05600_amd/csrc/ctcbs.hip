@@ -148,7 +148,8 @@ static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens)
   A(p.win_s, UW); A(p.win_e, UW);
   A(p.cand_id, UW * K); A(p.cand_inc, UW * K); A(p.cand_att, UW * K); A(p.cand_pre, UW * K);
   A(p.cand_ctc, UW * K); A(p.cand_joint, UW * K);
-  A(p.grp_n, UW); A(p.grp_idx, UW * Wb);
+  A(p.grp_n, UW); A(p.grp_J, UW * Wb); A(p.grp_ci, UW * Wb); A(p.grp_tok, UW * Wb);
+  A(p.grp_inc, UW * Wb); A(p.grp_att, UW * Wb);
   A(p.ctc_eos, UW); A(p.joint_eos, UW); A(p.stopped, UW); A(p.grp_cells, UW);
   A(p.utt, (size_t)U); A(p.finished, (size_t)U); A(p.cells, (size_t)U); A(p.groups, (size_t)U);
   A(p.n_finished, (size_t)1);
@@ -164,11 +165,10 @@ static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens)
   hipStream_t st = h->stream;
   HIPCHK(hipMemcpyAsync(d_lens, h->lens.data(), sizeof(int32_t) * U, hipMemcpyHostToDevice, st));
   HIPCHK(hipMemcpyAsync(d_lmax, h->lmax.data(), sizeof(int32_t) * U, hipMemcpyHostToDevice, st));
-  HIPCHK(hipMemsetAsync(p.xT, 0, sizeof(float) * (size_t)U * V * p.Tp, st));
   HIPCHK(hipMemsetAsync(p.grp_n, 0, sizeof(int32_t) * UW, st));
   HIPCHK(hipMemsetAsync(p.stopped, 0, sizeof(int32_t) * UW, st));
 
-  dim3 tg((V + 63) / 64, (c.t_max + 63) / 64, U);
+  dim3 tg((V + 63) / 64, (c.t_max + 4 + 63) / 64, U);
   hipLaunchKernelGGL(k_transpose, tg, dim3(256), 0, st, p, d_ctc_logp);
   HIPCHK(hipGetLastError());
   hipLaunchKernelGGL(k_init_state, dim3(U), dim3(64), 0, st, p);
@@ -182,11 +182,11 @@ static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens)
   size_t off = 0;
   sm.off_att = (int32_t)off; off += restricted ? (((size_t)V * 4 + 15) & ~(size_t)15) : 0;
   sm.off_work = (int32_t)off;
-  size_t work = (size_t)2 * p.Tp * 4;
-  if (restricted && work < (size_t)RADIX_BINS * 4) work = (size_t)RADIX_BINS * 4;
-  off += (work + 15) & ~(size_t)15;
+  off += restricted ? (size_t)RADIX_BINS * 4 : 0;
+  sm.off_f = (int32_t)off;
+  off += (size_t)2 * p.Tp * 4;                   // Tp is a multiple of 4: both arrays 16-byte aligned
   sm.off_small = (int32_t)off;
-  if (K <= h->score_block) off += (((size_t)K * 4 + 7) & ~(size_t)7) + (size_t)K * 8;
+  if (K <= h->score_block) off += (size_t)K * 20;
   sm.wp_max = p.Tp;
   h->score_smem_bytes = off;
   if (off > 160 * 1024) return CTCBS_EINVAL;
@@ -215,14 +215,14 @@ extern "C" int ctcbs_create(const ctcbs_config_t* cfg, const float* d_ctc_logp, 
   return CTCBS_OK;
 }
 
-template <int BLOCK, int LPC>
+template <int BLOCK, int LPC, int CB, int IT>
 static hipError_t launch_score(ctcbs* h, const float* att, int l) {
   if (h->score_smem_bytes > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute((const void*)k_score<BLOCK, LPC>,
+    hipError_t e = hipFuncSetAttribute((const void*)k_score<BLOCK, LPC, CB, IT>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->score_smem_bytes);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((k_score<BLOCK, LPC>), dim3(h->p.U * h->p.Wb), dim3(BLOCK), h->score_smem_bytes,
+  hipLaunchKernelGGL((k_score<BLOCK, LPC, CB, IT>), dim3(h->p.U * h->p.Wb), dim3(BLOCK), h->score_smem_bytes,
                      h->stream, h->p, h->sm, att, l, h->cur);
   return hipGetLastError();
 }
@@ -237,8 +237,10 @@ extern "C" int ctcbs_step(ctcbs_t* h, const float* d_att_logp, ctcbs_step_out_t*
     h->ev_used += 3;
     HIPCHK(hipEventRecord(ev[0], h->stream));
   }
-  hipError_t e = (h->score_lpc == 16) ? launch_score<256, 16>(h, d_att_logp, l)
-                                       : launch_score<256, 64>(h, d_att_logp, l);
+  // 16 lanes x 2 float4 per candidate cover windows of up to 128 frames without a second
+  // trip to memory; unrestricted windows use whole waves, 4 float4 (1024 frames) in flight
+  hipError_t e = (h->score_lpc == 16) ? launch_score<256, 16, 3, 2>(h, d_att_logp, l)
+                                       : launch_score<256, 64, 2, 4>(h, d_att_logp, l);
   HIPCHK(e);
   if (h->p.K > h->score_block) {
     hipLaunchKernelGGL((k_group_top<256>), dim3(h->p.U * h->p.Wb), dim3(256), 0, h->stream, h->p, h->cur);
@@ -283,8 +285,10 @@ extern "C" int ctcbs_finalize(ctcbs_t* h, int32_t* h_tokens, int32_t cap, int32_
                               int32_t* h_frames, int32_t* h_flags) {
   if (!h || !h_tokens || !h_ntok || !h_score || cap < 0) return CTCBS_EINVAL;
   const int U = h->p.U, rc_cap = h->res_cap;
-  hipLaunchKernelGGL(k_finalize, dim3((U + 63) / 64), dim3(64), 0, h->stream, h->p, h->cur, h->step, rc_cap,
-                     h->d_tokens, h->d_frames, h->d_ntok, h->d_score, h->d_flags);
+  const size_t fin_lds = (size_t)(h->l_cap + 1) * h->p.Wb + (size_t)h->l_cap + 1;
+  const int use_lds = fin_lds <= 60 * 1024;
+  hipLaunchKernelGGL((k_finalize<256>), dim3(U), dim3(256), use_lds ? fin_lds : 0, h->stream, h->p, h->cur,
+                     h->step, rc_cap, use_lds, h->d_tokens, h->d_frames, h->d_ntok, h->d_score, h->d_flags);
   HIPCHK(hipGetLastError());
   std::vector<int32_t> tok((size_t)U * rc_cap), frm((size_t)U * rc_cap), nt(U), fl(U);
   HIPCHK(hipMemcpyAsync(tok.data(), h->d_tokens, tok.size() * 4, hipMemcpyDeviceToHost, h->stream));

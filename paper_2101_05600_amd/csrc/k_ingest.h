@@ -4,13 +4,15 @@
 
 // CTC log-posteriors [U][t_max][V] (frame-major, as an encoder emits them) -> token-major
 // xT[u][k][t], t = 1..T_u, so that one candidate's frames are contiguous.  64x64 tiles
-// through LDS; frames at and beyond T_u are never read.
+// through LDS; frames at and beyond T_u are never read.  Index 0 and the four entries after
+// T_u are set to zero: aligned float4 loads of a window may touch them (their terms are
+// masked through the f array, which needs finite values there).
 __global__ __launch_bounds__(256) void k_transpose(Params p, const float* __restrict__ x) {
   __shared__ float tile[64][65];
   const int u = blockIdx.z;
   const int T = p.lens[u];
   const int t0 = blockIdx.y * 64, v0 = blockIdx.x * 64;
-  if (t0 >= T) return;
+  if (t0 >= T + 4) return;
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
   const float* src = x + (size_t)u * p.t_max * p.V;
 #pragma unroll 4
@@ -23,7 +25,11 @@ __global__ __launch_bounds__(256) void k_transpose(Params p, const float* __rest
 #pragma unroll 4
   for (int i = 0; i < 16; ++i) {
     int vv = v0 + ty * 16 + i, tt = t0 + tx;
-    if (vv < p.V && tt < T) dst[(size_t)vv * p.Tp + tt + 1] = tile[tx][ty * 16 + i];
+    if (vv < p.V) {
+      if (tt < T) dst[(size_t)vv * p.Tp + tt + 1] = tile[tx][ty * 16 + i];
+      else if (tt < T + 4) dst[(size_t)vv * p.Tp + tt + 1] = 0.0f;
+      if (tt == 0) dst[(size_t)vv * p.Tp] = 0.0f;
+    }
   }
 }
 

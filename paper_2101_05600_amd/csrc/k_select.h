@@ -8,6 +8,9 @@
 //     the recurrence evaluated as two wave-level scans of affine maps in the (logaddexp, +)
 //     semiring), their time indices tau / tau~ (first argmax from the parent's tau on);
 //   - back-pointer record and the step's outputs.
+// Everything the decisions need is fetched in one round of independent loads at the top
+// (old slots' records and the group lists); the only dependent second round is the
+// survivors' state and posterior columns.
 #pragma once
 #include "common.h"
 
@@ -30,103 +33,147 @@ template <int BLOCK>
 __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
   constexpr int NW = BLOCK / 64;
   constexpr int MAXE = MAX_BEAM * MAX_BEAM;
+  constexpr int EPT = (MAXE + BLOCK - 1) / BLOCK;
   __shared__ double s_J[MAXE];
-  __shared__ int s_par[MAXE], s_ci[MAXE];
+  __shared__ int s_par[MAXE], s_ci[MAXE], s_tok[MAXE];
+  __shared__ float s_inc[MAXE], s_att[MAXE];
   __shared__ int s_base[MAX_BEAM + 1];
   __shared__ int s_sel[MAX_BEAM];          // entry index of the new beam's slot n
+  // old slots' records
+  __shared__ int o_live[MAX_BEAM], o_n[MAX_BEAM], o_stp[MAX_BEAM], o_tau[MAX_BEAM], o_tau_end[MAX_BEAM];
+  __shared__ int o_rs[MAX_BEAM], o_re[MAX_BEAM], o_last[MAX_BEAM], o_ws[MAX_BEAM], o_we[MAX_BEAM];
+  __shared__ long long o_cells[MAX_BEAM];
+  __shared__ double o_je[MAX_BEAM], o_hatt[MAX_BEAM], o_off[MAX_BEAM];
   __shared__ int s_nnew, s_fin;
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int u = blockIdx.x, Wb = p.Wb, K = p.K;
+  const int u = blockIdx.x, Wb = p.Wb;
   if (p.finished[u]) return;               // outputs of a finished utterance were settled when it finished
   const int nxt = cur ^ 1;
   const size_t h0 = (size_t)u * Wb;
-  const int T = p.lens[u];
 
-  // ---- gather the groups' lists ----------------------------------------------------------
-  if (tid == 0) {
-    int acc = 0;
-    for (int j = 0; j < Wb; ++j) { s_base[j] = acc; acc += p.grp_n[h0 + j]; }
-    s_base[Wb] = acc;
+  // ---- round 1: every independent load ------------------------------------------------------
+  if (tid < Wb) {
+    const size_t h = h0 + tid;
+    o_live[tid] = p.h_live[cur][h]; o_n[tid] = p.grp_n[h]; o_stp[tid] = p.stopped[h];
+    o_tau[tid] = p.h_tau[cur][h]; o_tau_end[tid] = p.h_tau_end[cur][h];
+    o_rs[tid] = p.h_rs[cur][h]; o_re[tid] = p.h_re[cur][h]; o_last[tid] = p.h_last[cur][h];
+    o_ws[tid] = p.win_s[h]; o_we[tid] = p.win_e[h];
+    o_cells[tid] = p.grp_cells[h];
+    o_je[tid] = p.joint_eos[h]; o_hatt[tid] = p.h_att[cur][h]; o_off[tid] = p.h_off[cur][h];
+  }
+  const int T = p.lens[u];
+  const int lmax_u = p.lmax[u];
+  // utterance state, wave 0: lane 0 the scalars, lanes m < M the ring entries
+  UttState* us = p.utt + u;
+  double st_best = LOG0D, ring_sc = LOG0D;
+  int st_n = 0, st_cnt = 0, ring_tag = -1;
+  if (w == 0) {
+    if (lane == 0) { st_best = us->best_score; st_n = us->n_ended; st_cnt = us->cnt_tau_T; }
+    if (lane < p.end_m) { ring_sc = us->ring_score[lane]; ring_tag = us->ring_tag[lane]; }
+  }
+  // group lists: entry i = j * Wb + r of this utterance (Wb * Wb <= 1024 entries)
+  double eJ[EPT]; int eci[EPT], etok[EPT]; float einc[EPT], eatt[EPT];
+#pragma unroll
+  for (int k = 0; k < EPT; ++k) {
+    const int i = tid + k * BLOCK;
+    if (i < Wb * Wb) {
+      const size_t o = h0 * Wb + i;
+      eJ[k] = p.grp_J[o]; eci[k] = p.grp_ci[o]; etok[k] = p.grp_tok[o];
+      einc[k] = p.grp_inc[o]; eatt[k] = p.grp_att[o];
+    }
   }
   if (tid < MAX_BEAM) s_sel[tid] = -1;
   __syncthreads();
+  if (tid == 0) {
+    int acc = 0;
+    for (int j = 0; j < Wb; ++j) { s_base[j] = acc; acc += o_n[j]; }
+    s_base[Wb] = acc;
+  }
+  __syncthreads();
   const int ne = s_base[Wb];
-  for (int i = tid; i < Wb * Wb; i += BLOCK) {
-    int j = i / Wb, r = i % Wb;
-    if (r < p.grp_n[h0 + j]) {
-      int ci = p.grp_idx[(h0 + j) * Wb + r];
-      int e = s_base[j] + r;
-      s_J[e] = p.cand_joint[(h0 + j) * K + ci];
-      s_par[e] = j; s_ci[e] = ci;
+#pragma unroll
+  for (int k = 0; k < EPT; ++k) {
+    const int i = tid + k * BLOCK;
+    if (i < Wb * Wb) {
+      const int j = i / Wb, r = i % Wb;
+      if (r < o_n[j]) {
+        const int e = s_base[j] + r;
+        s_J[e] = eJ[k]; s_par[e] = j; s_ci[e] = eci[k]; s_tok[e] = etok[k];
+        s_inc[e] = einc[k]; s_att[e] = eatt[k];
+      }
     }
   }
   __syncthreads();
-  // ---- rank (entries of one parent are already in token order among equals) --------------
+  // ---- rank (total order: joint desc, parent slot asc, candidate index asc = token asc) -----
   for (int e = tid; e < ne; e += BLOCK) {
-    double me = s_J[e]; int mp = s_par[e], mc = s_ci[e];
+    const double me = s_J[e]; const int mp = s_par[e], mc = s_ci[e];
     int rank = 0;
     for (int o = 0; o < ne; ++o) {
-      double v = s_J[o];
+      const double v = s_J[o];
       rank += (v > me) || (v == me && (s_par[o] < mp || (s_par[o] == mp && s_ci[o] < mc)));
     }
     if (rank < Wb) s_sel[rank] = e;
   }
   __syncthreads();
 
-  // ---- ended set, end detection (one thread) ---------------------------------------------
-  if (tid == 0) {
+  // ---- ended set, end detection: wave 0, lane j = old slot j ---------------------------------
+  if (w == 0) {
     const int n_new = min(ne, Wb);
     const bool has_best = ne > 0;
     const double best = has_best ? s_J[s_sel[0]] : LOG0D;
-    const bool forced = (l >= p.lmax[u]);
-    UttState st = p.utt[u];
-    long long cells = 0, ngroups = 0;
-    for (int j = 0; j < Wb; ++j) {
-      const size_t h = h0 + j;
-      int added = 0, stp = 0;
-      if (p.h_live[cur][h]) {
-        cells += p.grp_cells[h];
-        ++ngroups;
-        stp = p.stopped[h];
-        const double je = p.joint_eos[h];
-        const bool je_ok = je > (double)LOG0_CLASS;
-        added = forced || stp || (je_ok && (!has_best || je > best));
-        if (added) {
-          if (st.n_ended == 0 || je > st.best_score) { st.best_score = je; st.best_step = l; st.best_slot = j; }
-          ++st.n_ended;
-          const int ri = l % p.end_m;
-          if (st.ring_tag[ri] != l) { st.ring_tag[ri] = l; st.ring_score[ri] = je; }
-          else if (je > st.ring_score[ri]) st.ring_score[ri] = je;
-          if (p.h_tau[cur][h] == T) ++st.cnt_tau_T;
-        }
-      }
-      p.out_eos_added[h] = (uint8_t)added;
-      p.out_stopped[h] = (uint8_t)stp;
+    const bool forced = (l >= lmax_u);
+    const bool mine = lane < Wb && o_live[lane];
+    const double je = mine ? o_je[lane] : LOG0D;
+    const int stp = mine ? o_stp[lane] : 0;
+    const bool je_ok = je > (double)LOG0_CLASS;
+    const bool added = mine && (forced || stp || (je_ok && (!has_best || je > best)));
+    long long cells = mine ? o_cells[lane] : 0;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) cells += __shfl_xor(cells, o);
+    const int ngroups = __popcll(__ballot(mine));
+    const int n_add = __popcll(__ballot(added));
+    const int n_tauT = __popcll(__ballot(added && o_tau[lane < Wb ? lane : 0] == T));
+    // best newly ended entry: largest score, lowest slot among equals (the one added first)
+    double bje = added ? je : -1.0e300; int bj = added ? lane : 0x7fffffff;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const double ov = __shfl_xor(bje, o); const int oj = __shfl_xor(bj, o);
+      if (ov > bje || (ov == bje && oj < bj)) { bje = ov; bj = oj; }
     }
+    if (lane < Wb) { p.out_eos_added[h0 + lane] = (uint8_t)added; p.out_stopped[h0 + lane] = (uint8_t)stp; }
+    const int n_before = __shfl(st_n, 0);
+    const int n_ended = n_before + n_add;
+    const int cnt = __shfl(st_cnt, 0) + n_tauT;
+    double ybest = __shfl(st_best, 0);
+    const bool new_best = n_add > 0 && (n_before == 0 || bje > ybest);
+    if (new_best) ybest = bje;
+    // ring of the best ended score per length (slot = length % M)
+    const int M = p.end_m;
+    const bool ring_upd = (lane == (l % M)) && n_add > 0;
+    if (ring_upd) { ring_tag = l; ring_sc = bje; }
     bool fin = forced || n_new == 0;
-    if (!fin && st.n_ended > 0) {
+    if (!fin && n_ended > 0) {
       if (p.end_flags & 1) {                       // Eq. (4)
-        int count = 0;
-        for (int m = 0; m < p.end_m; ++m) {
-          const int tag = l - m;
-          if (tag < 1) continue;
-          const int ri = tag % p.end_m;
-          if (st.ring_tag[ri] == tag && st.ring_score[ri] - st.best_score < (double)p.end_d) ++count;
-        }
-        if (count == p.end_m) fin = true;
+        const bool counts = lane < M && ring_tag >= 1 && ring_tag > l - M && ring_tag <= l &&
+                            (ring_sc - ybest < (double)p.end_d);
+        if (__popcll(__ballot(counts)) == M) fin = true;
       }
-      if (!fin && (p.end_flags & 2) && st.cnt_tau_T > p.end_c) fin = true;   // Algorithm 3
+      if (!fin && (p.end_flags & 2) && cnt > p.end_c) fin = true;   // Algorithm 3
     }
-    if (fin) {
-      st.finished_step = l;
-      p.finished[u] = 1;
-      atomicAdd(p.n_finished, 1);
+    if (ring_upd) { us->ring_tag[lane] = ring_tag; us->ring_score[lane] = ring_sc; }
+    if (lane == 0) {
+      us->n_ended = n_ended; us->cnt_tau_T = cnt;
+      if (new_best) { us->best_score = ybest; us->best_step = l; us->best_slot = bj; }
+      if (fin) {
+        us->finished_step = l;
+        p.finished[u] = 1;
+        atomicAdd(p.n_finished, 1);
+      }
+      p.cells[u] += (unsigned long long)cells;
+      p.groups[u] += (unsigned long long)ngroups;
+      s_nnew = n_new; s_fin = fin ? 1 : 0;
     }
-    p.utt[u] = st;
-    p.cells[u] += (unsigned long long)cells;
-    p.groups[u] += (unsigned long long)ngroups;
-    s_nnew = n_new; s_fin = fin ? 1 : 0;
   }
   __syncthreads();
   const int n_new = s_nnew;
@@ -137,17 +184,15 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
   for (int n = tid; n < Wb; n += BLOCK) {
     const size_t h = h0 + n;
     if (n < n_new) {
-      const int e = s_sel[n], par = s_par[e], ci = s_ci[e];
-      const size_t hp = h0 + par, cidx = hp * K + ci;
-      const int tok = p.cand_id[cidx];
+      const int e = s_sel[n], par = s_par[e], tok = s_tok[e];
       p.out_parent[h] = par; p.out_token[h] = tok; p.out_score[h] = (float)s_J[e];
       p.out_live[h] = fin ? 0 : 1;
       p.trie_parent[trie_l + n] = par; p.trie_token[trie_l + n] = tok;
       p.h_live[nxt][h] = fin ? 0 : 1;
       p.h_last[nxt][h] = tok;
-      p.h_rs[nxt][h] = p.win_s[hp]; p.h_re[nxt][h] = p.win_e[hp];
-      p.h_off[nxt][h] = p.cand_ctc[cidx];
-      p.h_att[nxt][h] = p.h_att[cur][hp] + (double)p.cand_att[cidx];
+      p.h_rs[nxt][h] = o_ws[par]; p.h_re[nxt][h] = o_we[par];
+      p.h_off[nxt][h] = o_off[par] + (double)s_inc[e];
+      p.h_att[nxt][h] = o_hatt[par] + (double)s_att[e];
       p.h_joint[nxt][h] = s_J[e];
     } else {
       p.out_parent[h] = -1; p.out_token[h] = -1; p.out_score[h] = LOG0F; p.out_live[h] = 0;
@@ -161,14 +206,13 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
   const float* xu = p.xT + (size_t)u * p.V * p.Tp;
   const float* x0 = xu + (size_t)p.blank_id * p.Tp;
   for (int n = w; n < n_new && !fin; n += NW) {
-    const int e = s_sel[n], par = s_par[e], ci = s_ci[e];
-    const size_t hp = h0 + par, cidx = hp * K + ci;
-    const int tok = p.cand_id[cidx];
-    const float inc = p.cand_inc[cidx];
-    const int s = p.win_s[hp], en = p.win_e[hp];
-    const int rs = p.h_rs[cur][hp], re = p.h_re[cur][hp];
-    const int ptau = p.h_tau[cur][hp], ptau_end = p.h_tau_end[cur][hp];
-    const bool rep = (tok == p.h_last[cur][hp]);
+    const int e = s_sel[n], par = s_par[e], tok = s_tok[e];
+    const size_t hp = h0 + par;
+    const float inc = s_inc[e];
+    const int s = o_ws[par], en = o_we[par];
+    const int rs = o_rs[par], re = o_re[par];
+    const int ptau = o_tau[par], ptau_end = o_tau_end[par];
+    const bool rep = (tok == o_last[par]);
     const float* pgn = p.gn[cur] + hp * p.Tp;
     const float* pgb = p.gb[cur] + hp * p.Tp;
     float* cgn = p.gn[nxt] + (h0 + n) * p.Tp;
@@ -186,7 +230,7 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
       if (valid) {
         const int pr = t - 1;
         float f = LOG0F;
-        if (pr >= rs && pr <= re) { float fb = pgb[pr]; f = rep ? fb : lae(pgn[pr], fb); }
+        if (pr >= rs && pr <= re) { const float fb = pgb[pr]; f = rep ? fb : lae(pgn[pr], fb); }
         const float x = xc[t];
         xb = x0[t];
         an.a = x; an.b = f + x;                  // n_t = (n_{t-1} (+) f_t) + x_t(c)

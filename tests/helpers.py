@@ -86,7 +86,8 @@ class GpuDecoder:
             self.h = None
 
 
-def lockstep_decode(w, ctc, lens, peek=True, check_utts=None, max_steps=None, progress=None):
+def lockstep_decode(w, ctc, lens, peek=True, check_utts=None, max_steps=None, progress=None,
+                    att_fn=None):
     """Decode the batch on the GPU with host-generated attention rows, validating every step of
     the utterances in check_utts (default: all) against the oracle.  Returns (report, results)."""
     U, Wb = len(lens), w["beam"]
@@ -104,6 +105,8 @@ def lockstep_decode(w, ctc, lens, peek=True, check_utts=None, max_steps=None, pr
             if max_steps is not None and step > max_steps:
                 break
             att = host_att(w, step, hashes, live, U)
+            if att_fn is not None:
+                att = att_fn(att)
             rc = dec.step(att)
             if rc == dec.m.DONE:
                 break

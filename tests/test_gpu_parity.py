@@ -56,6 +56,48 @@ def test_small_batches_ragged(variant):
     assert rep["exact_sel_steps"] >= 0.9 * rep["utt_steps"]
 
 
+def test_tied_attention_rows_take_the_radix_path():
+    """Coarsely quantised attention rows: thousands of equal values, ties resolved to smaller ids."""
+    w = small("cfg1", n_utt=3, t_lo=40, t_hi=90, vocab=3000, beam=4, cand_k=37, win_m1=20, win_m2=20,
+              end_flags=3)
+    lens, ctc = make_inputs(w)
+    rep, res = lockstep_decode(w, ctc, lens, att_fn=lambda a: np.where(np.isnan(a), a, np.round(a / 4) * 4),
+                               max_steps=12)
+    print(rep)
+    assert rep["utt_steps"] == 36 and rep["max_ctc_err"] < 1e-4
+    w2 = small("cfg1", n_utt=2, t_lo=30, t_hi=50, vocab=900, beam=3, cand_k=300, end_flags=3)
+    lens, ctc = make_inputs(w2)
+    rep, res = lockstep_decode(w2, ctc, lens, att_fn=lambda a: np.where(np.isnan(a), a, -1.0), max_steps=6)
+    assert rep["utt_steps"] == 12
+
+
+def test_finalize_equals_backtrack_of_step_outputs():
+    """Long utterance, wide beam: the trie walk that does not fit LDS; checked against the steps' own
+    parent/token outputs (no oracle involved)."""
+    w = small("cfg1", n_utt=2, t_lo=2300, t_hi=2400, vocab=64, beam=32, cand_k=0, win_m1=10, win_m2=10,
+              end_flags=0, max_len_ratio=0.0, max_len_abs=2290)
+    lens, ctc = make_inputs(w)
+    dec = GpuDecoder(w, ctc, lens)
+    rng = np.random.default_rng(1)
+    hist = []
+    att = rng.normal(size=(2, 32, 64)).astype(np.float32)
+    att[:, :, 63] = -1e4
+    for step in range(300):
+        assert dec.step(att) == dec.m.OK
+        if step % 50 == 49 or step < 3:
+            pass
+        out = dec.outputs()
+        hist.append((out["parent"].copy(), out["token"].copy(), out["tau"].copy()))
+    tok, nt, sc, frm, fl = dec.finalize(frames=True)
+    dec.close()
+    for u in range(2):
+        assert nt[u] == 300 and fl[u] == 1          # nothing ended: best live hypothesis
+        slot, want, want_f = 0, [], []
+        for par, tk, tau in reversed(hist):
+            want.append(tk[u, slot]); want_f.append(tau[u, slot]); slot = par[u, slot]
+        assert tok[u, :300].tolist() == want[::-1] and frm[u, :300].tolist() == want_f[::-1]
+
+
 def test_cfg1_shape_all_utterances():
     w = gen.workload("cfg1")
     lens, ctc = make_inputs(w)
