@@ -20,6 +20,14 @@
 #define MAX_EOS_RUN 32
 #define RADIX_BINS 4096
 
+// Phase time stamps for kernel tuning; compiled in only with -DCTCBS_TRACE (never in the
+// shipped library).
+#ifdef CTCBS_TRACE
+#define TRACE_POINT(p, blk, i) do { if ((p).trace && threadIdx.x == 0) (p).trace[(size_t)(blk) * 16 + (i)] = wall_clock64(); } while (0)
+#else
+#define TRACE_POINT(p, blk, i) do { } while (0)
+#endif
+
 struct UttState {            // per utterance, touched by one thread of the select kernel
   double best_score;         // best joint score in the ended set
   double ring_score[MAX_END_M];  // best ended score per length, lengths l, l-1, ... (ring by l % M)
@@ -94,6 +102,7 @@ struct Params {
   int32_t* out_tau_end;
   uint8_t* out_eos_added;
   uint8_t* out_stopped;
+  unsigned long long* trace; // [max(U*Wb, U)][16] per-block phase time stamps (tuning builds only)
 };
 
 __device__ __forceinline__ float lae(float a, float b) {
@@ -105,23 +114,48 @@ __device__ __forceinline__ float lae(float a, float b) {
 
 __device__ __forceinline__ float canon0(float v) { return v < LOG0_CLASS ? LOG0F : v; }
 
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+// ---- wave64 data movement through DPP (no LDS round trip) -----------------------------------
+// row_shr:n = 0x110+n and row_ror:n = 0x120+n act inside each row of 16 lanes; row_bcast:15
+// (0x142) / row_bcast:31 (0x143) copy the last lane of a row / of the lower half-wave into
+// the following row(s); wave_shr:1 = 0x138.  Lanes without a source keep `old`.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_i(int old, int src) {
+  return __builtin_amdgcn_update_dpp(old, src, CTRL, ROW_MASK, 0xf, false);
+}
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_f(float old, float src) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(src), CTRL, ROW_MASK,
+                                                    0xf, false));
+}
+
+// all-reduce inside each row of 16 lanes (commutative op through rotations)
+__device__ __forceinline__ float row16_max(float v) {
+  v = fmaxf(v, dpp_f<0x128, 0xf>(v, v));
+  v = fmaxf(v, dpp_f<0x124, 0xf>(v, v));
+  v = fmaxf(v, dpp_f<0x122, 0xf>(v, v));
+  v = fmaxf(v, dpp_f<0x121, 0xf>(v, v));
   return v;
 }
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_f<0x128, 0xf>(v, v);
+  v += dpp_f<0x124, 0xf>(v, v);
+  v += dpp_f<0x122, 0xf>(v, v);
+  v += dpp_f<0x121, 0xf>(v, v);
   return v;
 }
-__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v, int lane) {
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    uint32_t t = __shfl_up(v, o);
-    if (lane >= o) v += t;
-  }
-  return v;
+__device__ __forceinline__ float lane_f(float v, int lane) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+// inclusive prefix sum over the 64 lanes
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t x, int /*lane*/) {
+  int v = (int)x;
+  v += dpp_i<0x111, 0xf>(0, v);
+  v += dpp_i<0x112, 0xf>(0, v);
+  v += dpp_i<0x114, 0xf>(0, v);
+  v += dpp_i<0x118, 0xf>(0, v);
+  v += dpp_i<0x142, 0xa>(0, v);
+  v += dpp_i<0x143, 0xc>(0, v);
+  return (uint32_t)v;
 }
 
 // Exclusive prefix sum of one uint32 per thread over the block; *total = block sum.

@@ -157,6 +157,9 @@ static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens)
   A(p.trie_parent, trie_n); A(p.trie_token, trie_n); A(p.trie_tau, trie_n);
   A(p.out_parent, UW); A(p.out_token, UW); A(p.out_score, UW); A(p.out_live, UW);
   A(p.out_tau, UW); A(p.out_tau_end, UW); A(p.out_eos_added, UW); A(p.out_stopped, UW);
+#ifdef CTCBS_TRACE
+  A(p.trace, UW * 16);
+#endif
   h->res_cap = h->l_cap;
   A(h->d_tokens, (size_t)U * h->res_cap); A(h->d_frames, (size_t)U * h->res_cap);
   A(h->d_ntok, (size_t)U); A(h->d_flags, (size_t)U); A(h->d_score, (size_t)U);
@@ -385,6 +388,14 @@ extern "C" int ctcbs_peek(ctcbs_t* h, int32_t what, void* h_dst, size_t bytes, s
   }
   return CTCBS_OK;
 }
+
+#ifdef CTCBS_TRACE
+extern "C" int ctcbs_trace_read(ctcbs_t* h, unsigned long long* dst) {
+  HIPCHK(hipMemcpyAsync(dst, h->p.trace, (size_t)h->p.U * h->p.Wb * 16 * 8, hipMemcpyDeviceToHost, h->stream));
+  HIPCHK(hipStreamSynchronize(h->stream));
+  return CTCBS_OK;
+}
+#endif
 
 extern "C" void ctcbs_destroy(ctcbs_t* h) {
   if (!h) return;

@@ -32,22 +32,33 @@ __device__ __forceinline__ int f2ord(float v) {
 }
 
 // ---- candidate selection -----------------------------------------------------------------
-// Pivot path.  Returns false (uniformly) if more than PIVOT_CAP values reach the pivot.
+#define PIVOT_NPT 25   // ids per thread held in registers by the pivot path
+
+// Pivot path.  Returns false (uniformly) if the row does not fit (more than PIVOT_NPT ids per
+// thread) or more than PIVOT_CAP values reach the pivot.
 template <int BLOCK>
 __device__ __forceinline__ bool select_pivot(const float* s_att, int V, int K, int blank_id, int eos_id,
                                              uint32_t* s_key, int32_t* s_idx, uint32_t* s_scan,
-                                             uint32_t* s_w, int32_t* out_lds, int32_t* out_g) {
+                                             uint32_t* s_w, bool use_lds, int32_t* out_lds, int32_t* out_g) {
   constexpr int NW = BLOCK / 64;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int chunk = ((V + BLOCK - 1) / BLOCK) | 1;          // odd stride: conflict-free LDS reads
-  const int i0 = min(V, tid * chunk), i1 = min(V, i0 + chunk);
+  if (chunk > PIVOT_NPT) return false;
+  const int i0 = min(V, tid * chunk), nk = min(V, i0 + chunk) - i0;
+  uint32_t key[PIVOT_NPT];
   uint32_t lmax = 0;
-  for (int i = i0; i < i1; ++i) lmax = max(lmax, att_key(s_att[i], i, blank_id, eos_id));
-  // r-th largest chunk maximum of this wave, by bisection on the key bits
+#pragma unroll
+  for (int k = 0; k < PIVOT_NPT; ++k) {
+    const uint32_t kk = att_key(s_att[min(i0 + k, V - 1)], i0 + k, blank_id, eos_id);
+    key[k] = (k < nk) ? kk : 0u;
+    lmax = max(lmax, key[k]);
+  }
+  // r-th largest chunk maximum of this wave, by bisection on the upper 16 key bits (sign,
+  // exponent, 7 mantissa bits): stopping early only lowers the pivot, which stays valid
   const int r = (K + NW - 1) / NW;
   uint32_t thr = 0;
-#pragma unroll 1
-  for (int bit = 31; bit >= 0; --bit) {
+#pragma unroll 4
+  for (int bit = 31; bit >= 16; --bit) {
     const uint32_t trial = thr | (1u << bit);
     if (__popcll(__ballot(lmax >= trial)) >= r) thr = trial;
   }
@@ -58,30 +69,45 @@ __device__ __forceinline__ bool select_pivot(const float* s_att, int V, int K, i
   for (int i = 1; i < NW; ++i) L = min(L, s_w[i]);
   // at least NW * r >= K values are >= L; collect them in ascending id order
   uint32_t cnt = 0;
-  for (int i = i0; i < i1; ++i) cnt += att_key(s_att[i], i, blank_id, eos_id) >= L;
+#pragma unroll
+  for (int k = 0; k < PIVOT_NPT; ++k) cnt += (k < nk) && (key[k] >= L);
   uint32_t total;
   uint32_t pos = block_excl_scan_u32<BLOCK>(cnt, s_scan, &total);
   if (total > PIVOT_CAP) return false;
-  for (int i = i0; i < i1; ++i) {
-    const uint32_t k = att_key(s_att[i], i, blank_id, eos_id);
-    if (k >= L) { s_key[pos] = k; s_idx[pos] = i; ++pos; }
+#pragma unroll
+  for (int k = 0; k < PIVOT_NPT; ++k)
+    if ((k < nk) && key[k] >= L) { s_key[pos] = key[k]; s_idx[pos] = i0 + k; ++pos; }
+  const int n = (int)total;
+  const int n4 = (n + 3) >> 2;
+  if (tid < 4 && n + tid < 4 * n4) s_key[n + tid] = 0u;      // pad to a multiple of four
+  __syncthreads();
+  // exact rank by (key desc, id asc) = (key desc, list position asc): four lanes per entry,
+  // each comparing against a quarter of the list (uint4 reads), partial ranks summed by shuffle
+  int32_t* s_flag = s_idx + PIVOT_CAP;                        // [PIVOT_CAP] 1 = among the K best
+  const int part = tid & 3;
+  const uint4* s_key4 = (const uint4*)s_key;
+  for (int e = tid >> 2; e < ((n + BLOCK / 4 - 1) / (BLOCK / 4)) * (BLOCK / 4); e += BLOCK / 4) {
+    const uint32_t me = e < n ? s_key[e] : 0u;
+    int rank = 0;
+    for (int o4 = part; o4 < n4; o4 += 4) {
+      const uint4 v = s_key4[o4];
+      const int o = o4 * 4;
+      rank += (v.x > me) || (v.x == me && o < e);
+      rank += (v.y > me) || (v.y == me && o + 1 < e);
+      rank += (v.z > me) || (v.z == me && o + 2 < e);
+      rank += (v.w > me) || (v.w == me && o + 3 < e);
+    }
+    rank += __shfl_xor(rank, 1);
+    rank += __shfl_xor(rank, 2);
+    if (part == 0 && e < n) s_flag[e] = rank < K;
   }
   __syncthreads();
-  const int n = (int)total;
-  // exact rank by (key desc, id asc) = (key desc, list position asc); entries tid and tid + BLOCK
+  // ordered compaction of the flagged entries (entries tid and tid + BLOCK)
   uint32_t flags = 0;
 #pragma unroll
   for (int j = 0; j < PIVOT_CAP / BLOCK; ++j) {
     const int e = tid + j * BLOCK;
-    if (e < n) {
-      const uint32_t me = s_key[e];
-      int rank = 0;
-      for (int o = 0; o < n; ++o) {
-        const uint32_t v = s_key[o];
-        rank += (v > me) || (v == me && o < e);
-      }
-      if (rank < K) flags |= 1u << (16 * j);
-    }
+    if (e < n && s_flag[e]) flags |= 1u << (16 * j);
   }
   uint32_t tot2;
   const uint32_t ex = block_excl_scan_u32<BLOCK>(flags, s_scan, &tot2);
@@ -92,7 +118,7 @@ __device__ __forceinline__ bool select_pivot(const float* s_att, int V, int K, i
       const uint32_t o = j == 0 ? (ex & 0xffffu) : first_half + (ex >> 16);
       const int id = s_idx[tid + j * BLOCK];
       if (o < (uint32_t)K) {
-        if (out_lds) out_lds[o] = id;
+        if (use_lds) out_lds[o] = id;
         out_g[o] = id;
       }
     }
@@ -104,7 +130,7 @@ __device__ __forceinline__ bool select_pivot(const float* s_att, int V, int K, i
 template <int BLOCK>
 __device__ __noinline__ void select_radix(const float* s_att, int V, int K, int blank_id, int eos_id,
                                           uint32_t* s_hist, uint32_t* s_scan, uint32_t* s_sel,
-                                          int32_t* out_lds, int32_t* out_g) {
+                                          bool use_lds, int32_t* out_lds, int32_t* out_g) {
   const int tid = threadIdx.x;
   uint32_t prefix = 0, pmask = 0, krem = (uint32_t)K;
 #pragma unroll 1
@@ -161,7 +187,7 @@ __device__ __noinline__ void select_radix(const float* s_att, int V, int K, int 
     bool take = (k > prefix) || (k == prefix && eq_before < krem);
     if (k == prefix) ++eq_before;
     if (take && pos < (uint32_t)K) {
-      if (out_lds) out_lds[pos] = i;
+      if (use_lds) out_lds[pos] = i;
       out_g[pos] = i;
       ++pos;
     }
@@ -178,24 +204,23 @@ __device__ __forceinline__ void lse_add4(Lse& a, const float4 x, const float4 f)
   a.m = mn;
 }
 
-template <int LPC>
-__device__ __forceinline__ float lse_finish(Lse a) {
-  float M = a.m;
-#pragma unroll
-  for (int o = LPC / 2; o > 0; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
-  float s = a.s * __expf(a.m - M);
-#pragma unroll
-  for (int o = LPC / 2; o > 0; o >>= 1) s += __shfl_xor(s, o);
-  return (M < LOG0_CLASS) ? LOG0F : M + __logf(s);
+// the same, counting only frames <= t_cut (tb = frame of x.x)
+__device__ __forceinline__ void lse_add4_upto(Lse& a, const float4 x, const float4 f, int tb, int t_cut) {
+  const float v0 = tb <= t_cut ? f.x + x.x : LOG0F, v1 = tb + 1 <= t_cut ? f.y + x.y : LOG0F;
+  const float v2 = tb + 2 <= t_cut ? f.z + x.z : LOG0F, v3 = tb + 3 <= t_cut ? f.w + x.w : LOG0F;
+  const float mn = fmaxf(a.m, fmaxf(fmaxf(v0, v1), fmaxf(v2, v3)));
+  a.s = a.s * __expf(a.m - mn) + (__expf(v0 - mn) + __expf(v1 - mn)) + (__expf(v2 - mn) + __expf(v3 - mn));
+  a.m = mn;
 }
 
-// log-sum-exp over float4 groups [0, n4) of one column (used by the eos-run rule)
 template <int LPC>
-__device__ __forceinline__ float chain_lse(const float4* __restrict__ col, const float4* __restrict__ f4,
-                                           int n4, int q) {
-  Lse a; a.m = LOG0F; a.s = 0.0f;
-  for (int i = q; i < n4; i += LPC) lse_add4(a, col[i], f4[i]);
-  return lse_finish<LPC>(a);
+__device__ __forceinline__ float lse_finish(Lse a) {
+  static_assert(LPC == 16 || LPC == 64, "a candidate's lanes are one DPP row or one wave");
+  float M = row16_max(a.m);
+  if (LPC == 64) M = fmaxf(fmaxf(lane_f(M, 0), lane_f(M, 16)), fmaxf(lane_f(M, 32), lane_f(M, 48)));
+  float s = row16_sum(a.s * __expf(a.m - M));
+  if (LPC == 64) s = (lane_f(s, 0) + lane_f(s, 16)) + (lane_f(s, 32) + lane_f(s, 48));
+  return (M < LOG0_CLASS) ? LOG0F : M + __logf(s);
 }
 
 template <int BLOCK, int LPC, int CB, int IT>
@@ -205,7 +230,7 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
   __shared__ uint32_t s_scan[BLOCK / 64 + 1];
   __shared__ uint32_t s_w[BLOCK / 64];
   __shared__ uint32_t s_sel[2];
-  __shared__ int s_e2[MAX_EOS_RUN];
+  __shared__ float s_e2w[(BLOCK / 64) * MAX_EOS_RUN];
   __shared__ int s_nvalid;
 
   const int tid = threadIdx.x;
@@ -222,13 +247,14 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
     return;
   }
 
+  TRACE_POINT(p, grp, 0);
   float* s_att = (float*)(smem + sm.off_att);
   uint32_t* s_work = (uint32_t*)(smem + sm.off_work);
   float* s_F = (float*)(smem + sm.off_f);
   float* s_Fb = s_F + sm.wp_max;
   const int Ks = smallk ? K : 0;
   double* s_J = (double*)(smem + sm.off_small);
-  int32_t* s_cid = smallk ? (int32_t*)(s_J + Ks) : nullptr;
+  int32_t* s_cid = (int32_t*)(s_J + Ks);                  // only touched when smallk
   float* s_inc = (float*)(smem + sm.off_small) + 3 * Ks;    // after J (2 words each) and cand_id
   float* s_av = s_inc + Ks;
 
@@ -250,9 +276,26 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
   const float* gn = p.gn[cur] + (size_t)grp * p.Tp;
   const float* gb = p.gb[cur] + (size_t)grp * p.Tp;
 
+  TRACE_POINT(p, grp, 1);
   // ---------------- stage the attention row and the f terms (loads overlap) ---------------
-  if (p.restricted)
-    for (int i = tid; i < V; i += BLOCK) s_att[i] = arow[i];
+  if (p.restricted) {
+    if ((V & 3) == 0) {                                    // rows are 16-byte aligned: float4, 8 loads in flight
+      const float4* a4 = (const float4*)arow;
+      float4* s4 = (float4*)s_att;
+      const int nv4 = V >> 2;
+      for (int base = 0; base < nv4; base += BLOCK * 8) {
+        // clamped, unconditional loads and stores: all eight loads are in flight together; lanes
+        // past the row's end rewrite its last float4 with the same value
+        float4 r[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) r[k] = a4[min(base + tid + k * BLOCK, nv4 - 1)];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) s4[min(base + tid + k * BLOCK, nv4 - 1)] = r[k];
+      }
+    } else {
+      for (int i = tid; i < V; i += BLOCK) s_att[i] = arow[i];
+    }
+  }
   for (int i = tid; i < Wp; i += BLOCK) {
     const int t = t0 + i;
     float f = LOG0F, fb = LOG0F;
@@ -265,14 +308,14 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
   const int R = p.eos_run;
   const bool e2 = (p.end_flags & 4) && R > 0 && T >= R && W > 0 && e == T && re == T &&
                   max(s, rs) <= T - R + 1;
-  if (e2 && tid < R) s_e2[tid] = f2ord(LOG0F) - 1;
   __syncthreads();
+  TRACE_POINT(p, grp, 2);
 
   // ---------------- 1. candidates -----------------------------------------------------------
   if (p.restricted) {
     const bool ok = select_pivot<BLOCK>(s_att, V, K, p.blank_id, p.eos_id, s_work, (int32_t*)(s_work + PIVOT_CAP),
-                                        s_scan, s_w, s_cid, g_cid);
-    if (!ok) select_radix<BLOCK>(s_att, V, K, p.blank_id, p.eos_id, s_work, s_scan, s_sel, s_cid, g_cid);
+                                        s_scan, s_w, smallk, s_cid, g_cid);
+    if (!ok) select_radix<BLOCK>(s_att, V, K, p.blank_id, p.eos_id, s_work, s_scan, s_sel, smallk, s_cid, g_cid);
   } else {
     const int lo_ex = min(p.blank_id, p.eos_id), hi_ex = max(p.blank_id, p.eos_id);
     for (int i = tid; i < K; i += BLOCK) {
@@ -282,6 +325,7 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
     }
   }
   __syncthreads();                                         // candidate ids visible to the whole block
+  TRACE_POINT(p, grp, 3);
 
   // ---------------- 3. prefix scores ----------------------------------------------------
   constexpr int NSG = BLOCK / LPC;
@@ -301,10 +345,8 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
       ids[b] = (c < K) ? (smallk ? s_cid[c] : g_cid[c]) : -1;
       const float4* col = (const float4*)(xu + (size_t)(ids[b] < 0 ? 0 : ids[b]) * p.Tp + t0);
 #pragma unroll
-      for (int it = 0; it < IT; ++it) {
-        const int i = q + it * LPC;
-        x[b][it] = (ids[b] >= 0 && i < n4) ? col[i] : make_float4(0.f, 0.f, 0.f, 0.f);
-      }
+      for (int it = 0; it < IT; ++it)                        // unconditional (clamped) loads: all in flight together
+        x[b][it] = col[min(q + it * LPC, max(n4 - 1, 0))];
     }
 #pragma unroll
     for (int b = 0; b < CB; ++b) {
@@ -312,14 +354,24 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
       if (ids[b] < 0) continue;                            // uniform over the LPC lanes of a chain
       const int id = ids[b];
       const float4* col = (const float4*)(xu + (size_t)id * p.Tp + t0);
-      const float4* f4 = (const float4*)((id == last) ? s_Fb : s_F);
+      const float4* f4 = (const float4*)(s_F + ((id == last) ? sm.wp_max : 0));   // Fb follows F
       Lse a; a.m = LOG0F; a.s = 0.0f;
+      Lse ap = a;                                          // eos-run rule: the sum without the last R frames
+      const int t_cut = T - R;
 #pragma unroll
       for (int it = 0; it < IT; ++it) {
         const int i = q + it * LPC;
-        if (i < n4) lse_add4(a, x[b][it], f4[i]);
+        if (i < n4) {
+          const float4 f = f4[i];
+          lse_add4(a, x[b][it], f);
+          if (e2) lse_add4_upto(ap, x[b][it], f, t0 + 4 * i, t_cut);
+        }
       }
-      for (int i = q + IT * LPC; i < n4; i += LPC) lse_add4(a, col[i], f4[i]);
+      for (int i = q + IT * LPC; i < n4; i += LPC) {
+        const float4 xv = col[i], f = f4[i];
+        lse_add4(a, xv, f);
+        if (e2) lse_add4_upto(ap, xv, f, t0 + 4 * i, t_cut);
+      }
       const float inc = (W > 0) ? lse_finish<LPC>(a) : LOG0F;
       if (q == 0) {
         const float av = p.restricted ? s_att[id] : arow[id];
@@ -330,21 +382,13 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
         if (smallk) { s_J[c] = (valid && J == J) ? J : LOG0D; s_inc[c] = inc; s_av[c] = av; }
       }
       if (e2) {
-        // running prefix score up to frame T-R: same sum with the last R frames cut off
-        // (the cut is not float4-aligned: the last partial float4 is added term by term)
-        const int t_cut = T - R;                           // last frame included
-        float pre = LOG0F;
-        if (t_cut >= s) {
-          const int full4 = (t_cut + 1 - t0) >> 2;         // float4 groups entirely <= t_cut
-          pre = chain_lse<LPC>(col, f4, full4, q);
-          const float* colf = (const float*)col; const float* ff = (const float*)f4;
-          for (int i = full4 * 4; t0 + i <= t_cut; ++i) pre = lae(pre, ff[i] + colf[i]);
-        }
+        const float pre = lse_finish<LPC>(ap);             // running prefix score at frame T-R
         if (q == 0) p.cand_pre[(size_t)grp * K + c] = pre;
       }
     }
   }
 
+  TRACE_POINT(p, grp, 4);
   // ---------------- 4. eos, eos-run rule, group list -------------------------------------
   if (tid == 0) {
     float ce = LOG0F;
@@ -359,33 +403,50 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
   int fire = 0;
   if (e2) {
     __syncthreads();                                       // cand_pre written by this block
+    float xmax[MAX_EOS_RUN];                               // per frame: best running prefix score seen by this lane
+#pragma unroll
+    for (int k = 0; k < MAX_EOS_RUN; ++k) xmax[k] = -3.0e38f;
     for (int c = tid; c < K; c += BLOCK) {
       const int id = smallk ? s_cid[c] : g_cid[c];
       const float* colf = xu + (size_t)id * p.Tp;
-      const float* ff = (id == last) ? s_Fb : s_F;
+      const float* ff = s_F + ((id == last) ? sm.wp_max : 0);
+      float xv[MAX_EOS_RUN];
+#pragma unroll
+      for (int k = 0; k < MAX_EOS_RUN; ++k) xv[k] = colf[min(T - R + 1 + k, T)];   // all loads in flight
       float acc = p.cand_pre[(size_t)grp * K + c];
-      for (int k = 0; k < R; ++k) {
-        const int t = T - R + 1 + k;
-        acc = lae(acc, ff[t - t0] + colf[t]);
-        atomicMax(&s_e2[k], f2ord(canon0(acc)));
+#pragma unroll
+      for (int k = 0; k < MAX_EOS_RUN; ++k) {
+        if (k < R) {
+          const int t = T - R + 1 + k;
+          acc = lae(acc, ff[t - t0] + xv[k]);
+          xmax[k] = fmaxf(xmax[k], canon0(acc));
+        }
       }
     }
-    __syncthreads();
-    if (tid == 0) {
-      fire = 1;
-      for (int k = 0; k < R; ++k) {
-        const int t = T - R + 1 + k;
-        const float Et = canon0(lae(gn[t], gb[t]));
-        const int Xo = s_e2[k];
-        // E_t > X_t with log0 on the left never true, log0 on the right always true
-        const bool gt = (Et > LOG0_CLASS) && (Xo < f2ord(LOG0_CLASS) || f2ord(Et) > Xo);
-        if (!gt) fire = 0;
+#pragma unroll
+    for (int k = 0; k < MAX_EOS_RUN; ++k) {                // max over the wave, one slot per wave and frame
+      if (k < R) {
+        float v = row16_max(xmax[k]);
+        v = fmaxf(fmaxf(lane_f(v, 0), lane_f(v, 16)), fmaxf(lane_f(v, 32), lane_f(v, 48)));
+        if ((tid & 63) == 0) s_e2w[(tid >> 6) * MAX_EOS_RUN + k] = v;
       }
-      p.stopped[grp] = fire;
-      s_e2[0] = fire;
+    }
+    if (tid == 0) s_nvalid = 1;                            // reused as the "all frames passed" flag
+    __syncthreads();
+    if (tid < R) {
+      const int t = T - R + 1 + tid;
+      const float Et = canon0(lae(gn[t], gb[t]));
+      float X = s_e2w[tid];
+#pragma unroll
+      for (int w2 = 1; w2 < BLOCK / 64; ++w2) X = fmaxf(X, s_e2w[w2 * MAX_EOS_RUN + tid]);
+      // E_t > X_t with log0 on the left never true, log0 on the right always true
+      const bool gt = (Et > LOG0_CLASS) && (X < LOG0_CLASS || Et > X);
+      if (!gt) s_nvalid = 0;                               // every writer stores the same value
     }
     __syncthreads();
-    fire = s_e2[0];
+    fire = s_nvalid;
+    if (tid == 0) p.stopped[grp] = fire;
+    __syncthreads();                                       // s_nvalid is reset below
   } else if (tid == 0) {
     p.stopped[grp] = 0;
   }
@@ -394,25 +455,32 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
     // rank by (joint desc, candidate index asc); candidate index order is token order
     if (tid == 0) s_nvalid = 0;
     __syncthreads();                                       // s_J complete
-    if (tid < K && !fire) {
-      const double me = s_J[tid];
-      if (me > (double)LOG0_CLASS) {
+    if (!fire) {
+      const int part = tid & 3;
+      for (int e0 = 0; e0 < K; e0 += BLOCK / 4) {          // four lanes per candidate
+        const int e = e0 + (tid >> 2);
+        const double me = e < K ? s_J[e] : LOG0D;
         int rank = 0;
-        for (int c = 0; c < K; ++c) {
+        for (int c = part; c < K; c += 4) {
           const double o = s_J[c];
-          rank += (o > me) || (o == me && c < tid);
+          rank += (o > me) || (o == me && c < e);
         }
-        if (rank < p.Wb) {
-          const size_t o = (size_t)grp * p.Wb + rank;
-          p.grp_J[o] = me; p.grp_ci[o] = tid; p.grp_tok[o] = s_cid[tid];
-          p.grp_inc[o] = s_inc[tid]; p.grp_att[o] = s_av[tid];
+        rank += __shfl_xor(rank, 1);
+        rank += __shfl_xor(rank, 2);
+        if (part == 0 && e < K && me > (double)LOG0_CLASS) {
+          if (rank < p.Wb) {
+            const size_t o = (size_t)grp * p.Wb + rank;
+            p.grp_J[o] = me; p.grp_ci[o] = e; p.grp_tok[o] = s_cid[e];
+            p.grp_inc[o] = s_inc[e]; p.grp_att[o] = s_av[e];
+          }
+          atomicAdd(&s_nvalid, 1);
         }
-        atomicAdd(&s_nvalid, 1);
       }
     }
     __syncthreads();
     if (tid == 0) p.grp_n[grp] = fire ? 0 : min(s_nvalid, p.Wb);
   }
+  TRACE_POINT(p, grp, 5);
 }
 
 // Group list for large candidate sets (K > block size): Wb rounds of a block-wide argmax

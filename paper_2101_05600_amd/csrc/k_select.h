@@ -20,13 +20,43 @@ __device__ __forceinline__ Aff aff_then(Aff first, Aff second) {
   Aff r; r.a = first.a + second.a; r.b = lae(first.b + second.a, second.b); return r;
 }
 
-__device__ __forceinline__ Aff wave_scan_aff(Aff v, int lane) {
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    Aff left; left.a = __shfl_up(v.a, o); left.b = __shfl_up(v.b, o);
-    if (lane >= o) v = aff_then(left, v);
-  }
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ Aff aff_stage(Aff v) {
+  Aff left;                                 // lanes without a source get the identity map
+  left.a = dpp_f<CTRL, ROW_MASK>(0.0f, v.a);
+  left.b = dpp_f<CTRL, ROW_MASK>(LOG0F, v.b);
+  return aff_then(left, v);
+}
+
+// inclusive scan of affine maps over the wave: lane t ends with map_0 then ... then map_t
+__device__ __forceinline__ Aff wave_scan_aff(Aff v) {
+  v = aff_stage<0x111, 0xf>(v);
+  v = aff_stage<0x112, 0xf>(v);
+  v = aff_stage<0x114, 0xf>(v);
+  v = aff_stage<0x118, 0xf>(v);
+  v = aff_stage<0x142, 0xa>(v);
+  v = aff_stage<0x143, 0xc>(v);
   return v;
+}
+
+struct ArgMax { float v; int t; };
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ ArgMax argmax_stage(ArgMax x) {
+  const float ov = dpp_f<CTRL, ROW_MASK>(-3.0e38f, x.v);
+  const int ot = dpp_i<CTRL, ROW_MASK>(0x7fffffff, x.t);
+  if (ov > x.v || (ov == x.v && ot < x.t)) { x.v = ov; x.t = ot; }
+  return x;
+}
+// largest value, earliest frame among equals; result valid in lane 63
+__device__ __forceinline__ ArgMax wave_argmax(ArgMax x) {
+  x = argmax_stage<0x111, 0xf>(x);
+  x = argmax_stage<0x112, 0xf>(x);
+  x = argmax_stage<0x114, 0xf>(x);
+  x = argmax_stage<0x118, 0xf>(x);
+  x = argmax_stage<0x142, 0xa>(x);
+  x = argmax_stage<0x143, 0xc>(x);
+  x.v = lane_f(x.v, 63); x.t = __builtin_amdgcn_readlane(x.t, 63);
+  return x;
 }
 
 template <int BLOCK>
@@ -51,6 +81,7 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
   if (p.finished[u]) return;               // outputs of a finished utterance were settled when it finished
   const int nxt = cur ^ 1;
   const size_t h0 = (size_t)u * Wb;
+  TRACE_POINT(p, u, 8);
 
   // ---- round 1: every independent load ------------------------------------------------------
   if (tid < Wb) {
@@ -85,6 +116,7 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
   }
   if (tid < MAX_BEAM) s_sel[tid] = -1;
   __syncthreads();
+  TRACE_POINT(p, u, 9);
   if (tid == 0) {
     int acc = 0;
     for (int j = 0; j < Wb; ++j) { s_base[j] = acc; acc += o_n[j]; }
@@ -106,17 +138,25 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
   }
   __syncthreads();
   // ---- rank (total order: joint desc, parent slot asc, candidate index asc = token asc) -----
-  for (int e = tid; e < ne; e += BLOCK) {
-    const double me = s_J[e]; const int mp = s_par[e], mc = s_ci[e];
+  // eight lanes per entry, each comparing against an eighth of the list
+  for (int e0 = 0; e0 < ne; e0 += BLOCK / 8) {
+    const int e = e0 + (tid >> 3), part = tid & 7;
+    const bool have = e < ne;
+    const double me = have ? s_J[e] : LOG0D;
+    // equal scores: entries are stored in (parent slot, token) order, so the position decides
     int rank = 0;
-    for (int o = 0; o < ne; ++o) {
+    for (int o = part; o < ne; o += 8) {
       const double v = s_J[o];
-      rank += (v > me) || (v == me && (s_par[o] < mp || (s_par[o] == mp && s_ci[o] < mc)));
+      rank += (v > me) || (v == me && o < e);
     }
-    if (rank < Wb) s_sel[rank] = e;
+    rank += __shfl_xor(rank, 1);
+    rank += __shfl_xor(rank, 2);
+    rank += __shfl_xor(rank, 4);
+    if (part == 0 && have && rank < Wb) s_sel[rank] = e;
   }
   __syncthreads();
 
+  TRACE_POINT(p, u, 10);
   // ---- ended set, end detection: wave 0, lane j = old slot j ---------------------------------
   if (w == 0) {
     const int n_new = min(ne, Wb);
@@ -178,6 +218,7 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
   __syncthreads();
   const int n_new = s_nnew;
   const bool fin = s_fin != 0;
+  TRACE_POINT(p, u, 11);
 
   // ---- new beam: records, outputs, back-pointers ------------------------------------------
   const size_t trie_l = ((size_t)l * p.U + u) * Wb;
@@ -202,6 +243,7 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
     }
   }
 
+  TRACE_POINT(p, u, 12);
   // ---- forward variables of the new hypotheses --------------------------------------------
   const float* xu = p.xT + (size_t)u * p.V * p.Tp;
   const float* x0 = xu + (size_t)p.blank_id * p.Tp;
@@ -222,44 +264,51 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
     float carry_n = LOG0F, carry_b = LOG0F;
     float best_n = LOG0F, best_b = LOG0F;
     int arg_n = ptau, arg_b = ptau_end;
-    for (int base = s; base <= en; base += 64) {
-      const int t = base + lane;
-      const bool valid = t <= en;
-      Aff an, ab;
-      float xb = 0.0f;
-      if (valid) {
-        const int pr = t - 1;
-        float f = LOG0F;
-        if (pr >= rs && pr <= re) { const float fb = pgb[pr]; f = rep ? fb : lae(pgn[pr], fb); }
-        const float x = xc[t];
-        xb = x0[t];
-        an.a = x; an.b = f + x;                  // n_t = (n_{t-1} (+) f_t) + x_t(c)
-      } else { an.a = 0.0f; an.b = LOG0F; }
-      an = wave_scan_aff(an, lane);
-      const float nt = lae(an.a + carry_n, an.b);
-      float nprev = __shfl_up(nt, 1);
-      if (lane == 0) nprev = carry_n;
-      if (valid) { ab.a = xb; ab.b = nprev + xb; }   // b_t = (n_{t-1} (+) b_{t-1}) + x_t(blank)
-      else { ab.a = 0.0f; ab.b = LOG0F; }
-      ab = wave_scan_aff(ab, lane);
-      const float bt = lae(ab.a + carry_b, ab.b);
-      carry_n = __shfl(nt, 63); carry_b = __shfl(bt, 63);
+    // 128 frames per pass: each lane owns two consecutive frames, composes their two affine
+    // maps, the wave scans the composed maps, and the lane then replays its own two frames
+    for (int base = s; base <= en; base += 128) {
+      const int ta = base + 2 * lane, tb = ta + 1;
+      const bool va = ta <= en, vb = tb <= en;
+      const int tac = min(ta, en), tbc = min(tb, en);      // clamped: loads are unconditional
+      const float gna = pgn[max(tac - 1, 0)], gba = pgb[max(tac - 1, 0)];
+      const float gnb = pgn[tbc - 1], gbb = pgb[tbc - 1];
+      const float xa = xc[tac], xb = xc[tbc], x0a = x0[tac], x0b = x0[tbc];
+      float fa = LOG0F, fb = LOG0F;
+      if (ta - 1 >= rs && ta - 1 <= re) fa = rep ? gba : lae(gna, gba);
+      if (tb - 1 >= rs && tb - 1 <= re) fb = rep ? gbb : lae(gnb, gbb);
+      Aff ma, mb;                                          // n_t = (n_{t-1} (+) f_t) + x_t(c)
+      ma.a = va ? xa : 0.0f; ma.b = va ? fa + xa : LOG0F;
+      mb.a = vb ? xb : 0.0f; mb.b = vb ? fb + xb : LOG0F;
+      Aff P = wave_scan_aff(aff_then(ma, mb));
+      Aff E;                                               // maps of all earlier lanes
+      E.a = dpp_f<0x138, 0xf>(0.0f, P.a); E.b = dpp_f<0x138, 0xf>(LOG0F, P.b);
+      const float n_in = lae(E.a + carry_n, E.b);
+      const float na = lae(n_in + ma.a, ma.b);
+      const float nb = lae(na + mb.a, mb.b);
+      ma.a = va ? x0a : 0.0f; ma.b = va ? n_in + x0a : LOG0F;   // b_t = (n_{t-1} (+) b_{t-1}) + x_t(blank)
+      mb.a = vb ? x0b : 0.0f; mb.b = vb ? na + x0b : LOG0F;
+      P = wave_scan_aff(aff_then(ma, mb));
+      E.a = dpp_f<0x138, 0xf>(0.0f, P.a); E.b = dpp_f<0x138, 0xf>(LOG0F, P.b);
+      const float b_in = lae(E.a + carry_b, E.b);
+      const float ba = lae(b_in + ma.a, ma.b);
+      const float bb = lae(ba + mb.a, mb.b);
+      carry_n = lane_f(nb, 63); carry_b = lane_f(bb, 63);
       // re-base on the child's own prefix score and store
-      const float rn = (nt < LOG0_CLASS) ? LOG0F : nt - inc;
-      const float rb = (bt < LOG0_CLASS) ? LOG0F : bt - inc;
-      if (valid) { cgn[t] = rn; cgb[t] = rb; }
+      const float rna = (na < LOG0_CLASS) ? LOG0F : na - inc, rnb = (nb < LOG0_CLASS) ? LOG0F : nb - inc;
+      const float rba = (ba < LOG0_CLASS) ? LOG0F : ba - inc, rbb = (bb < LOG0_CLASS) ? LOG0F : bb - inc;
+      if (va) { cgn[ta] = rna; cgb[ta] = rba; }
+      if (vb) { cgn[tb] = rnb; cgb[tb] = rbb; }
       // first argmax over t >= lo
-      float vn = (valid && t >= lo) ? rn : LOG0F, vb = (valid && t >= lo) ? rb : LOG0F;
-      int tn = t, tb = t;
-#pragma unroll
-      for (int o = 32; o > 0; o >>= 1) {
-        float ov = __shfl_xor(vn, o); int ot = __shfl_xor(tn, o);
-        if (ov > vn || (ov == vn && ot < tn)) { vn = ov; tn = ot; }
-        ov = __shfl_xor(vb, o); ot = __shfl_xor(tb, o);
-        if (ov > vb || (ov == vb && ot < tb)) { vb = ov; tb = ot; }
-      }
+      const float ca = (va && ta >= lo) ? rna : LOG0F, cb = (vb && tb >= lo) ? rnb : LOG0F;
+      const float da = (va && ta >= lo) ? rba : LOG0F, db = (vb && tb >= lo) ? rbb : LOG0F;
+      ArgMax xn, xb2;
+      xn.v = cb > ca ? cb : ca; xn.t = cb > ca ? tb : ta;
+      xb2.v = db > da ? db : da; xb2.t = db > da ? tb : ta;
+      xn = wave_argmax(xn); xb2 = wave_argmax(xb2);
+      const float vn = xn.v, vbv = xb2.v;
+      const int tn = xn.t, tbt = xb2.t;
       if (vn > LOG0_CLASS && vn > best_n) { best_n = vn; arg_n = tn; }
-      if (vb > LOG0_CLASS && vb > best_b) { best_b = vb; arg_b = tb; }
+      if (vbv > LOG0_CLASS && vbv > best_b) { best_b = vbv; arg_b = tbt; }
     }
     if (lane == 0) {
       p.h_tau[nxt][h0 + n] = arg_n; p.h_tau_end[nxt][h0 + n] = arg_b;
@@ -267,4 +316,6 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
       p.trie_tau[trie_l + n] = arg_n;
     }
   }
+  __syncthreads();
+  TRACE_POINT(p, u, 13);
 }
