@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--poll-every", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=24, help="utterances in the oracle's timed sample")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (known traffic, for scaling rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -74,8 +77,9 @@ class Batch:
             l = min(l, w["max_len_abs"])
         return max(l, 1)
 
-    def record(self):
-        """Untimed decode that produces (and keeps) every step's attention rows."""
+    def record(self, observer=None):
+        """Untimed decode that produces (and keeps) every step's attention rows.
+        observer(step, att_rows_of_step, handle, step_out): optional hook after every step (tests)."""
         torch, m, gen, w = self.torch, self.m, self.gen, self.w
         U, Wb, V = self.U, self.Wb, self.V
         self.att = torch.empty((self.l_cap, U, Wb, V), dtype=torch.float32, device="cuda")
@@ -98,6 +102,8 @@ class Batch:
                 if m.ctcbs_step(h, self.att[step - 1], out) == m.DONE:
                     step -= 1
                     break
+                if observer is not None:
+                    observer(step, self.att[step - 1], h, out)
                 if out.n_finished == U:
                     break
             self.n_steps = step
@@ -201,6 +207,13 @@ def main():
     w = gen.workload(a.workload)
     b = Batch(w, a.poll_every)
     ref = b.record()
+    if a.calib_copy:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                       # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(a.warmup):
         b.decode()
     torch.cuda.synchronize()
@@ -221,13 +234,14 @@ def main():
     # the parent's two forward variables 8 B per window frame, the attention row 4V per group
     bytes_score = 4.0 * b.cells + 8.0 * b.cells / K + (4.0 * w["vocab"] * b.groups if restricted else 0.0)
     ach = bytes_score / (score_ms * 1e-3) / 1e9
+    # measured HBM bytes per launch of the same kernel (rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by a
+    # plain copy): taken from the committed counter summary, not measurable from inside this process
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"k_score_{a.workload}_traffic.json")
+    tpath = os.path.join(ROOT, "profiles", f"k_score_{a.workload}_traffic.txt")
     if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get("traffic_bytes_per_launch")
-        except Exception:
-            traffic = None
+        for ln in open(tpath):
+            if ln.startswith("traffic_bytes_per_launch:"):
+                traffic = float(ln.split(":")[1])
     line = {
         "metric": "CTC prefix-score cells/sec (utt·beam·cand·frame) + utterances/sec at B=64",
         "value": b.cells / (dt / a.steps), "unit": "cells/s",

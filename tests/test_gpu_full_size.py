@@ -1,0 +1,87 @@
+"""Parity at the benchmark's full size and launch configuration (cfg2: U=64, V=5000, beam 10, top-40,
+window 50/50, all end rules), on sampled utterances that the oracle follows step by step.
+
+Inputs are the device generator's bytes (the same ones bench.py times), copied back for the oracle."""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+sys.path.insert(0, ROOT)
+
+import gen
+from helpers import orc_cfg_from
+from oracle.lockstep import Lockstep
+
+pytestmark = pytest.mark.gpu
+
+
+def run_sampled(workload, sample, over=None):
+    import bench
+    import paper_2101_05600_amd as m
+    w = gen.workload(workload)
+    if over:
+        w.update(over)
+    b = bench.Batch(w, poll_every=8)
+    U, Wb, K = b.U, b.Wb, w["cand_k"]
+    xs = [b.d_ctc[u, :b.lens[u]].cpu().numpy() for u in sample]
+    ls = Lockstep(xs, orc_cfg_from(w), utt_ids=sample)
+    g = lambda p, shape, dt: m.view(p, shape, dt).cpu().numpy()
+
+    def observer(step, att_step, h, o):
+        out = dict(parent=g(o.d_parent, (U, Wb), np.int32), token=g(o.d_token, (U, Wb), np.int32),
+                   score=g(o.d_score, (U, Wb), np.float32), live=g(o.d_live, (U, Wb), np.uint8),
+                   finished=g(o.d_finished, (U,), np.uint8), tau=g(o.d_tau, (U, Wb), np.int32),
+                   tau_end=g(o.d_tau_end, (U, Wb), np.int32),
+                   eos_added=g(o.d_eos_added, (U, Wb), np.uint8),
+                   stopped=g(o.d_stopped, (U, Wb), np.uint8))
+        pk = lambda what: m.ctcbs_peek(h, what)
+        peek = dict(cand_id=pk(m.PEEK_CAND_ID).reshape(U, Wb, K),
+                    cand_ctc=pk(m.PEEK_CAND_CTC).reshape(U, Wb, K),
+                    cand_joint=pk(m.PEEK_CAND_JOINT).reshape(U, Wb, K),
+                    win_s=pk(m.PEEK_WIN_S).reshape(U, Wb), win_e=pk(m.PEEK_WIN_E).reshape(U, Wb),
+                    ctc_eos=pk(m.PEEK_CTC_EOS).reshape(U, Wb), joint_eos=pk(m.PEEK_JOINT_EOS).reshape(U, Wb))
+        att = {u: att_step[u].cpu().numpy() for u in sample if not ls.utts[sample.index(u)].finished}
+        for u in sample:
+            att.setdefault(u, None)
+        ls.step(att, out, peek)
+        if step % 50 == 0:
+            print(f"step {step}: {ls.report}", flush=True)
+
+    tok, nt, sc, frm, fl = b.record(observer)
+    ls.check_results(tok, nt, sc, fl)
+    # the timed path (recorded rows replayed, polling every 8 steps) reproduces the recorded decode
+    (tok2, nt2, sc2, _, fl2), _ = b.decode()
+    assert np.array_equal(tok, tok2) and np.array_equal(nt, nt2) and np.array_equal(sc, sc2)
+    assert all(o.finished for o in ls.utts)
+    return ls.report, b
+
+
+def test_cfg2_full_size_sampled_utterances():
+    w = gen.workload("cfg2")
+    lens = gen.workload_lengths(w)
+    order = np.argsort(lens)
+    sample = sorted({int(order[0]), int(order[-1]), int(order[len(order) // 2]), 5, 40})
+    rep, b = run_sampled("cfg2", sample)
+    print(rep, "decode steps", b.n_steps, "cells", b.cells)
+    assert rep["max_score_err"] < 1e-4 and rep["max_ctc_err"] < 1e-4
+    assert rep["utt_steps"] > 400
+
+
+def test_cfg3_one_batch_of_meeting_segments():
+    """One batch of 128 Korean-meeting-like segments (V=2300), the four longest and shortest followed."""
+    seg = gen.segments(2101)
+    assert seg.max() <= 500
+    w = gen.workload("cfg3")
+    lens = seg[-128:]                       # the batch of the 128 longest segments (sorted by length)
+    import bench
+    orig = gen.workload_lengths
+    try:
+        gen.workload_lengths = lambda _w: np.ascontiguousarray(lens, dtype=np.int32)
+        rep, b = run_sampled("cfg3", [0, 1, 126, 127])
+    finally:
+        gen.workload_lengths = orig
+    print(rep)
+    assert rep["max_score_err"] < 1e-4 and rep["max_ctc_err"] < 1e-4
