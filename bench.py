@@ -104,9 +104,10 @@ class Batch:
                     break
                 if observer is not None:
                     observer(step, self.att[step - 1], h, out)
-                if out.n_finished == U:
+                if m.ctcbs_poll(h) == U:           # untimed pass: blocking, exact
                     break
             self.n_steps = step
+            self.att_ptr = [self.att[i].data_ptr() for i in range(self.l_cap)]
             res = m.ctcbs_finalize(h, U, self.l_cap)
             stats = m.ctcbs_stats(h)
         finally:
@@ -123,8 +124,10 @@ class Batch:
         try:
             if profile:
                 m.ctcbs_profile(h, True)
-            for step in range(1, self.n_steps + 1):
-                if m.ctcbs_step(h, self.att[step - 1], out) == m.DONE:
+            # the loop a caller without foreknowledge runs: step until the library reports that every
+            # utterance has finished (it looks every poll_every steps without draining the stream)
+            for step in range(1, self.l_cap + 1):
+                if m.ctcbs_step(h, self.att_ptr[min(step, self.n_steps) - 1], out) == m.DONE:
                     break
                 if out.n_finished == U:
                     break

@@ -17,7 +17,8 @@
  * code on failure (nothing is thrown, nothing aborts) and ctcbs_step may return the
  * positive CTCBS_DONE.  All device work is enqueued on the stream given at creation; the
  * only host synchronisations are inside ctcbs_create (end), ctcbs_finalize,
- * ctcbs_poll/ctcbs_peek/ctcbs_stats and the optional periodic poll of ctcbs_step.
+ * ctcbs_poll/ctcbs_peek/ctcbs_stats/ctcbs_profile_read; the optional periodic look of
+ * ctcbs_step only waits for work enqueued two intervals earlier.
  * A handle is not thread-safe.
  */
 #ifndef CTCBS_H
@@ -56,8 +57,9 @@ enum {
 
 /*
  * Search configuration (Algorithm 2's inputs plus the constants of Sec. 3.2).
- * Limits: 1 <= beam <= 32; 3 <= vocab; with 0 < cand_k < vocab-2 the vocabulary must not
- * exceed 12288 ids; 1 <= t_max <= 6140; end_m <= 8; eos_run <= 32.
+ * Limits: 1 <= beam <= 32; 3 <= vocab; 1 <= t_max <= 6140; end_m <= 8; eos_run <= 32.
+ * (With 0 < cand_k < vocab-2 the fast candidate selection needs vocab to be a multiple of 4
+ * and at most 6144; other vocabularies take a slower, equivalent path.)
  */
 typedef struct {
   int32_t n_utt;        /* U                                                               */
@@ -81,8 +83,10 @@ typedef struct {
   float end_d;          /* log-domain D_end of Eq. (4) (paper: -10)                        */
   int32_t end_c;        /* C of Algorithm 3 (paper: 2)                                     */
   int32_t eos_run;      /* frames of the CTCBS_END_EOS_RUN rule (10)                       */
-  int32_t poll_every;   /* > 0: every that many steps ctcbs_step synchronises and reads the
-                           count of finished utterances; 0: never                          */
+  int32_t poll_every;   /* > 0: every that many steps ctcbs_step looks, without draining the
+                           stream, at the count of finished utterances the device has
+                           published (it may lag by up to two such intervals) and keeps the
+                           host from running further ahead than that; 0: never             */
   void* stream;         /* hipStream_t; NULL = the null stream                             */
 } ctcbs_config_t;
 
@@ -92,7 +96,8 @@ typedef struct {
  */
 typedef struct {
   int32_t step;             /* l of the step just enqueued                                 */
-  int32_t n_finished;       /* finished utterances if this call polled, else -1            */
+  int32_t n_finished;       /* finished utterances as last published by the device if this
+                               call looked (see poll_every; a lower bound), else -1          */
   const int32_t* d_parent;  /* [U][Wb] old beam slot each new hypothesis extends (GatherB)  */
   const int32_t* d_token;   /* [U][Wb] label appended                                      */
   const float* d_score;     /* [U][Wb] joint score, Eq. (1) (+ length bonus)               */
@@ -123,7 +128,8 @@ int ctcbs_create(const ctcbs_config_t* cfg, const float* d_ctc_logp, const int32
  * step only slot 0 of each utterance is live.  The buffer must stay valid until the step's
  * work has run on the stream.  `out` may be NULL.
  * Returns CTCBS_DONE (and enqueues nothing) once the handle knows that all utterances are
- * finished: after a poll saw it, or when the step index passes every utterance's cap.
+ * finished: after a look or ctcbs_poll saw it, or when the step index passes every
+ * utterance's cap.  Steps enqueued after the last utterance finished do nothing.
  */
 int ctcbs_step(ctcbs_t* h, const float* d_att_logp, ctcbs_step_out_t* out);
 
@@ -164,7 +170,7 @@ int ctcbs_profile_read(ctcbs_t* h, double* score_ms, double* select_ms, int32_t*
  * full size in *need (may be NULL).
  */
 enum {
-  CTCBS_PEEK_CAND_ID = 1,    /* int32  [U][Wb][K] candidate ids, ascending per group        */
+  CTCBS_PEEK_CAND_ID = 1,    /* int32  [U][Wb][K] candidate ids (no particular order)       */
   CTCBS_PEEK_CAND_CTC = 2,   /* double [U][Wb][K] log psi(g.c), Eq. (3)/(5)                 */
   CTCBS_PEEK_CAND_JOINT = 3, /* double [U][Wb][K] joint score of g.c                        */
   CTCBS_PEEK_WIN_S = 4,      /* int32  [U][Wb] window start s                               */

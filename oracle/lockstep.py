@@ -75,15 +75,16 @@ class Lockstep:
                     if peek["win_s"][u, j] != s_o[j] or peek["win_e"][u, j] != e_o[j]:
                         self._fail(u, l, f"window of slot {j}: {peek['win_s'][u, j]},{peek['win_e'][u, j]} "
                                          f"vs oracle {s_o[j]},{e_o[j]}")
-                    if not np.array_equal(peek["cand_id"][u, j], ids_o[j]):
+                    perm = np.argsort(peek["cand_id"][u, j], kind="stable")   # the other side's order is free
+                    if not np.array_equal(peek["cand_id"][u, j][perm], ids_o[j]):
                         self._fail(u, l, f"candidate ids of slot {j} differ")
                     for i in range(o.K):
-                        a, b = float(peek["cand_ctc"][u, j, i]), float(ctc_o[j, i])
+                        a, b = float(peek["cand_ctc"][u, j, perm[i]]), float(ctc_o[j, i])
                         if not _close(a, b, eps):
                             self._fail(u, l, f"ctc prefix score slot {j} cand {ids_o[j, i]}: {a} vs {b}")
                         if not _is0(b):
                             rep["max_ctc_err"] = max(rep["max_ctc_err"], abs(a - b))
-                        a, b = float(peek["cand_joint"][u, j, i]), float(J_o[j, i])
+                        a, b = float(peek["cand_joint"][u, j, perm[i]]), float(J_o[j, i])
                         if not _close(a, b, eps):
                             self._fail(u, l, f"joint score slot {j} cand {ids_o[j, i]}: {a} vs {b}")
                     for name, ref in (("ctc_eos", ce_o), ("joint_eos", je_o)):

@@ -18,7 +18,6 @@
 #define MAX_BEAM 32
 #define MAX_END_M 8
 #define MAX_EOS_RUN 32
-#define RADIX_BINS 4096
 
 // Phase time stamps for kernel tuning; compiled in only with -DCTCBS_TRACE (never in the
 // shipped library).
@@ -89,6 +88,7 @@ struct Params {
   unsigned long long* cells; // [U] prefix-score terms so far
   unsigned long long* groups;// [U] live (utterance, beam) groups so far
   int32_t* n_finished;       // [1]
+  int32_t* host_finished;    // [1] host-resident copy (device-mapped pinned memory), one step behind
   // back-pointer trie, level l holds the hypotheses of length l: [l_cap+1][U][Wb]
   int32_t* trie_parent;
   int32_t* trie_token;

@@ -40,6 +40,12 @@ struct ctcbs {
   int32_t *d_tokens, *d_frames, *d_ntok, *d_flags;
   float* d_score;
   int32_t res_cap;
+  // non-blocking progress: pinned, device-mapped word the score kernel refreshes every step, and
+  // two events that keep the host at most two poll intervals ahead of the device
+  int32_t* h_flag;
+  hipEvent_t throttle[2];
+  bool throttle_made, throttle_armed[2];
+  int32_t throttle_k;
   // optional per-kernel timing
   bool profiling;
   std::vector<hipEvent_t> events;   // 3 per recorded step: before score, after score, after select
@@ -61,6 +67,11 @@ static int dev_alloc(ctcbs* h, T** out, size_t n) {
 static void free_all(ctcbs* h) {
   for (void* q : h->allocs) (void)hipFree(q);
   h->allocs.clear();
+  if (h->h_flag) { (void)hipHostFree(h->h_flag); h->h_flag = nullptr; }
+  if (h->throttle_made) {
+    (void)hipEventDestroy(h->throttle[0]); (void)hipEventDestroy(h->throttle[1]);
+    h->throttle_made = false;
+  }
 }
 
 static int step_cap(const ctcbs_config_t* c, int T) {
@@ -93,7 +104,6 @@ static int validate(const ctcbs_config_t* c) {
       c->blank_id == c->eos_id) return CTCBS_EINVAL;
   if (c->cand_k < 0) return CTCBS_EINVAL;
   bool restricted = c->cand_k > 0 && c->cand_k < c->vocab - 2;
-  if (restricted && c->vocab > 12288) return CTCBS_EINVAL;
   if (!(c->ctc_weight >= 0.0f && c->ctc_weight <= 1.0f)) return CTCBS_EINVAL;
   if (c->length_bonus != c->length_bonus || c->max_len_ratio != c->max_len_ratio || c->max_len_ratio < 0.0f)
     return CTCBS_EINVAL;
@@ -165,6 +175,19 @@ static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens)
   A(h->d_ntok, (size_t)U); A(h->d_flags, (size_t)U); A(h->d_score, (size_t)U);
 #undef A
 
+  {
+    void* hp = nullptr;
+    hipError_t e = hipHostMalloc(&hp, 64, hipHostMallocMapped);
+    if (e != hipSuccess) { g_last_hip = (int)e; (void)hipGetLastError(); return CTCBS_ENOMEM; }
+    h->h_flag = (int32_t*)hp;
+    *h->h_flag = 0;
+    void* dp = nullptr;
+    HIPCHK(hipHostGetDevicePointer(&dp, hp, 0));
+    p.host_finished = (int32_t*)dp;
+    HIPCHK(hipEventCreateWithFlags(&h->throttle[0], hipEventDisableTiming));
+    HIPCHK(hipEventCreateWithFlags(&h->throttle[1], hipEventDisableTiming));
+    h->throttle_made = true;
+  }
   hipStream_t st = h->stream;
   HIPCHK(hipMemcpyAsync(d_lens, h->lens.data(), sizeof(int32_t) * U, hipMemcpyHostToDevice, st));
   HIPCHK(hipMemcpyAsync(d_lmax, h->lmax.data(), sizeof(int32_t) * U, hipMemcpyHostToDevice, st));
@@ -183,9 +206,8 @@ static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens)
   h->score_lpc = windowed ? 16 : 64;
   ScoreSmem& sm = h->sm;
   size_t off = 0;
-  sm.off_att = (int32_t)off; off += restricted ? (((size_t)V * 4 + 15) & ~(size_t)15) : 0;
   sm.off_work = (int32_t)off;
-  off += restricted ? (size_t)RADIX_BINS * 4 : 0;
+  off += restricted ? (size_t)PIVOT_CAP * 12 : 0;       // short list (key, id, flag); also holds the radix histogram
   sm.off_f = (int32_t)off;
   off += (size_t)2 * p.Tp * 4;                   // Tp is a multiple of 4: both arrays 16-byte aligned
   sm.off_small = (int32_t)off;
@@ -198,6 +220,7 @@ static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens)
 
   h->step = 0; h->cur = 0; h->known_finished = 0;
   h->profiling = false; h->ev_used = 0;
+  h->throttle_k = 0; h->throttle_armed[0] = h->throttle_armed[1] = false;
   HIPCHK(hipStreamSynchronize(st));
   return CTCBS_OK;
 }
@@ -210,6 +233,7 @@ extern "C" int ctcbs_create(const ctcbs_config_t* cfg, const float* d_ctc_logp, 
   if (rc != CTCBS_OK) return rc;
   ctcbs* h = new (std::nothrow) ctcbs();
   if (!h) return CTCBS_ENOMEM;
+  h->h_flag = nullptr; h->throttle_made = false;
   h->cfg = *cfg;
   h->stream = (hipStream_t)cfg->stream;
   rc = create_impl(h, d_ctc_logp, h_lens);
@@ -261,8 +285,14 @@ extern "C" int ctcbs_step(ctcbs_t* h, const float* d_att_logp, ctcbs_step_out_t*
   h->cur ^= 1;
   int polled = -1;
   if (h->cfg.poll_every > 0 && (l % h->cfg.poll_every) == 0) {
-    int rc = ctcbs_poll(h, &polled);
-    if (rc != CTCBS_OK) return rc;
+    // wait (normally not at all) for the interval before the last one, then look at the count the
+    // device has published; the device keeps at least one interval of queued work meanwhile
+    const int k = h->throttle_k++;
+    if (h->throttle_armed[(k + 1) & 1]) HIPCHK(hipEventSynchronize(h->throttle[(k + 1) & 1]));
+    HIPCHK(hipEventRecord(h->throttle[k & 1], h->stream));
+    h->throttle_armed[k & 1] = true;
+    polled = *(volatile int32_t*)h->h_flag;
+    h->known_finished = polled;
   }
   if (out) {
     const Params& p = h->p;

@@ -1,9 +1,11 @@
 // Score kernel: one work-group per (utterance, beam slot) hypothesis g.
 //   1. candidate pre-selection: the K ids with the largest attention log-prob, ties to the
-//      smaller id, output in ascending id order.  Fast path: a pivot L that is provably not
-//      above the K-th largest value (every wave contributes the ceil(K/#waves)-th largest of
-//      its lanes' chunk maxima), then an exact ranking of the few values >= L.  Rows with so
-//      many values >= L that the short list overflows (heavy ties) take a radix select.
+//      smaller id.  The row never goes through LDS: every lane keeps its float4 loads as
+//      order-preserving keys in registers.  Fast path: a pivot L that is provably not above
+//      the K-th largest value (every wave contributes the ceil(K/#waves)-th largest of its
+//      lanes' maxima, found by bisection on the upper key bits), then an exact ranking of the
+//      few values >= L.  Rows that do not fit the registers, or with so many values >= L that
+//      the short list overflows (heavy ties), take a radix select that re-reads the row.
 //   2. window [s, e] from g's time indices (the two equations after Eq. (5));
 //   3. prefix score of every extension g.c: log-sum over t in [s, e] of
 //      f_t + log p^c(z_t = c), f_t = blank variable of g at t-1 if c repeats g's last label,
@@ -12,48 +14,48 @@
 //      is consumed, streaming log-sum-exp with one exp per term;
 //   4. eos score phi_T(g), joint scores (Eq. (1)), the eos-run test, and the group's
 //      best-first list of at most Wb candidates for the per-utterance selection.
+// The candidate list of a group is in no particular (but reproducible) order; wherever
+// equal scores must be ordered the token id decides.
 #pragma once
 #include "common.h"
 
-#define PIVOT_CAP 512
+#define PIVOT_CAP 512     // entries of the short list
+#define PIVOT_NV4 6       // float4 loads per lane held in registers (rows of up to 6144 ids)
+#define RADIX_BITS 10
 
 struct ScoreSmem {
   // byte offsets into dynamic LDS, computed on the host
-  int32_t off_att;    // float[V]           attention row (restricted mode)
-  int32_t off_work;   // union: uint32 hist[RADIX_BINS] | { uint32 key[PIVOT_CAP]; int32 idx[PIVOT_CAP] }
+  int32_t off_work;   // union: uint32 hist[1 << RADIX_BITS] | { uint32 key[CAP]; int32 idx[CAP]; int32 flag[CAP] }
   int32_t off_f;      // float F[wp_max], Fb[wp_max]
   int32_t off_small;  // double J[Ks]; int32 cand_id[Ks]; float inc[Ks], att[Ks]  (Ks = K if K <= BLOCK else 0)
   int32_t wp_max;     // floats available per F array
 };
 
-__device__ __forceinline__ int f2ord(float v) {
-  int i = __float_as_int(v);
-  return i >= 0 ? i : i ^ 0x7fffffff;
+__device__ __forceinline__ float key_to_att(uint32_t k) {
+  return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
 }
 
 // ---- candidate selection -----------------------------------------------------------------
-#define PIVOT_NPT 25   // ids per thread held in registers by the pivot path
-
-// Pivot path.  Returns false (uniformly) if the row does not fit (more than PIVOT_NPT ids per
-// thread) or more than PIVOT_CAP values reach the pivot.
+// Pivot path on the lane's register-resident row values (v[k] = ids 4 * (tid + k * BLOCK) ..+3;
+// excluded ids and ids past the row's end hold -inf).  Comparisons run on the floats
+// themselves; only each lane's maximum and the few collected values are turned into
+// order-preserving keys.  Returns false (uniformly) if the short list would overflow or, with
+// NaNs in the row, would hold fewer than K values.  Writes the K ids (and their attention
+// values) in short-list order.
 template <int BLOCK>
-__device__ __forceinline__ bool select_pivot(const float* s_att, int V, int K, int blank_id, int eos_id,
-                                             uint32_t* s_key, int32_t* s_idx, uint32_t* s_scan,
-                                             uint32_t* s_w, bool use_lds, int32_t* out_lds, int32_t* out_g) {
+__device__ __forceinline__ bool select_pivot(const float4 (&v)[PIVOT_NV4], int K, int blank_id, int eos_id,
+                                             uint32_t* s_key, int32_t* s_idx, int32_t* s_flag,
+                                             uint32_t* s_scan, uint32_t* s_w, bool use_lds, int32_t* out_lds,
+                                             float* out_att_lds, int32_t* out_g) {
   constexpr int NW = BLOCK / 64;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int chunk = ((V + BLOCK - 1) / BLOCK) | 1;          // odd stride: conflict-free LDS reads
-  if (chunk > PIVOT_NPT) return false;
-  const int i0 = min(V, tid * chunk), nk = min(V, i0 + chunk) - i0;
-  uint32_t key[PIVOT_NPT];
-  uint32_t lmax = 0;
+  const float ninf = -__builtin_huge_valf();
+  float fmx = ninf;
 #pragma unroll
-  for (int k = 0; k < PIVOT_NPT; ++k) {
-    const uint32_t kk = att_key(s_att[min(i0 + k, V - 1)], i0 + k, blank_id, eos_id);
-    key[k] = (k < nk) ? kk : 0u;
-    lmax = max(lmax, key[k]);
-  }
-  // r-th largest chunk maximum of this wave, by bisection on the upper 16 key bits (sign,
+  for (int k = 0; k < PIVOT_NV4; ++k)
+    fmx = fmaxf(fmx, fmaxf(fmaxf(v[k].x, v[k].y), fmaxf(v[k].z, v[k].w)));
+  const uint32_t lmax = att_key(fmx, -1, -2, -2);
+  // r-th largest lane maximum of this wave, by bisection on the upper 16 key bits (sign,
   // exponent, 7 mantissa bits): stopping early only lowers the pivot, which stays valid
   const int r = (K + NW - 1) / NW;
   uint32_t thr = 0;
@@ -64,38 +66,52 @@ __device__ __forceinline__ bool select_pivot(const float* s_att, int V, int K, i
   }
   if (lane == 0) s_w[w] = thr;
   __syncthreads();
-  uint32_t L = s_w[0];
+  uint32_t Lk = s_w[0];
 #pragma unroll
-  for (int i = 1; i < NW; ++i) L = min(L, s_w[i]);
-  // at least NW * r >= K values are >= L; collect them in ascending id order
+  for (int i = 1; i < NW; ++i) Lk = min(Lk, s_w[i]);
+  // at least NW * r >= K values are >= L (as a float: -inf if no wave had r finite maxima)
+  const float L = Lk <= att_key(ninf, -1, -2, -2) ? ninf : key_to_att(Lk);
   uint32_t cnt = 0;
 #pragma unroll
-  for (int k = 0; k < PIVOT_NPT; ++k) cnt += (k < nk) && (key[k] >= L);
+  for (int k = 0; k < PIVOT_NV4; ++k)
+    cnt += (v[k].x >= L) + (v[k].y >= L) + (v[k].z >= L) + (v[k].w >= L);
   uint32_t total;
   uint32_t pos = block_excl_scan_u32<BLOCK>(cnt, s_scan, &total);
-  if (total > PIVOT_CAP) return false;
+  if (total > PIVOT_CAP || total < (uint32_t)K) return false;
+  if (cnt) {
 #pragma unroll
-  for (int k = 0; k < PIVOT_NPT; ++k)
-    if ((k < nk) && key[k] >= L) { s_key[pos] = key[k]; s_idx[pos] = i0 + k; ++pos; }
+    for (int k = 0; k < PIVOT_NV4; ++k) {
+      const float e[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (e[j] >= L) {
+          const int id = 4 * (tid + k * BLOCK) + j;
+          s_key[pos] = att_key(e[j], id, blank_id, eos_id);     // excluded ids (held as -inf) rank last
+          s_idx[pos] = id;
+          ++pos;
+        }
+    }
+  }
   const int n = (int)total;
   const int n4 = (n + 3) >> 2;
-  if (tid < 4 && n + tid < 4 * n4) s_key[n + tid] = 0u;      // pad to a multiple of four
+  if (tid < 4 && n + tid < 4 * n4) { s_key[n + tid] = 0u; s_idx[n + tid] = 0x7fffffff; }   // pad to a multiple of four
   __syncthreads();
-  // exact rank by (key desc, id asc) = (key desc, list position asc): four lanes per entry,
-  // each comparing against a quarter of the list (uint4 reads), partial ranks summed by shuffle
-  int32_t* s_flag = s_idx + PIVOT_CAP;                        // [PIVOT_CAP] 1 = among the K best
+  // exact rank by (key desc, id asc): four lanes per entry, each comparing against a quarter of
+  // the list (uint4 reads), partial ranks summed by shuffle
   const int part = tid & 3;
   const uint4* s_key4 = (const uint4*)s_key;
+  const int4* s_idx4 = (const int4*)s_idx;
   for (int e = tid >> 2; e < ((n + BLOCK / 4 - 1) / (BLOCK / 4)) * (BLOCK / 4); e += BLOCK / 4) {
     const uint32_t me = e < n ? s_key[e] : 0u;
+    const int mid = e < n ? s_idx[e] : 0x7fffffff;
     int rank = 0;
     for (int o4 = part; o4 < n4; o4 += 4) {
-      const uint4 v = s_key4[o4];
-      const int o = o4 * 4;
-      rank += (v.x > me) || (v.x == me && o < e);
-      rank += (v.y > me) || (v.y == me && o + 1 < e);
-      rank += (v.z > me) || (v.z == me && o + 2 < e);
-      rank += (v.w > me) || (v.w == me && o + 3 < e);
+      const uint4 kv = s_key4[o4];
+      const int4 d = s_idx4[o4];
+      rank += (kv.x > me) || (kv.x == me && d.x < mid);
+      rank += (kv.y > me) || (kv.y == me && d.y < mid);
+      rank += (kv.z > me) || (kv.z == me && d.z < mid);
+      rank += (kv.w > me) || (kv.w == me && d.w < mid);
     }
     rank += __shfl_xor(rank, 1);
     rank += __shfl_xor(rank, 2);
@@ -118,7 +134,7 @@ __device__ __forceinline__ bool select_pivot(const float* s_att, int V, int K, i
       const uint32_t o = j == 0 ? (ex & 0xffffu) : first_half + (ex >> 16);
       const int id = s_idx[tid + j * BLOCK];
       if (o < (uint32_t)K) {
-        if (use_lds) out_lds[o] = id;
+        if (use_lds) { out_lds[o] = id; out_att_lds[o] = key_to_att(s_key[tid + j * BLOCK]); }
         out_g[o] = id;
       }
     }
@@ -126,24 +142,25 @@ __device__ __forceinline__ bool select_pivot(const float* s_att, int V, int K, i
   return true;
 }
 
-// Radix select on the order-preserving keys (12 + 12 + 8 bits), ordered compaction.
+// Radix select on the order-preserving keys (10 + 10 + 10 + 2 bits) straight from the row in
+// global memory, then an ordered compaction (ascending ids).
 template <int BLOCK>
-__device__ __noinline__ void select_radix(const float* s_att, int V, int K, int blank_id, int eos_id,
+__device__ __noinline__ void select_radix(const float* __restrict__ arow, int V, int K, int blank_id, int eos_id,
                                           uint32_t* s_hist, uint32_t* s_scan, uint32_t* s_sel,
-                                          bool use_lds, int32_t* out_lds, int32_t* out_g) {
+                                          bool use_lds, int32_t* out_lds, float* out_att_lds, int32_t* out_g) {
   const int tid = threadIdx.x;
   uint32_t prefix = 0, pmask = 0, krem = (uint32_t)K;
 #pragma unroll 1
-  for (int pass = 0; pass < 3; ++pass) {
-    const int shift = pass == 0 ? 20 : (pass == 1 ? 8 : 0);
-    const int bits = pass == 2 ? 8 : 12;
+  for (int pass = 0; pass < 4; ++pass) {
+    const int shift = pass == 0 ? 22 : (pass == 1 ? 12 : (pass == 2 ? 2 : 0));
+    const int bits = pass == 3 ? 2 : RADIX_BITS;
     const uint32_t bmask = (1u << bits) - 1u;
     const int nb = 1 << bits;
     __syncthreads();
     for (int i = tid; i < nb; i += BLOCK) s_hist[i] = 0;
     __syncthreads();
     for (int i = tid; i < V; i += BLOCK) {
-      uint32_t k = att_key(s_att[i], i, blank_id, eos_id);
+      uint32_t k = att_key(arow[i], i, blank_id, eos_id);
       if ((k & pmask) == prefix) atomicAdd(&s_hist[(k >> shift) & bmask], 1u);
     }
     __syncthreads();
@@ -175,7 +192,7 @@ __device__ __noinline__ void select_radix(const float* s_att, int V, int K, int 
   const int i0 = min(V, tid * chunk), i1 = min(V, i0 + chunk);
   uint32_t gt = 0, eq = 0;
   for (int i = i0; i < i1; ++i) {
-    uint32_t k = att_key(s_att[i], i, blank_id, eos_id);
+    uint32_t k = att_key(arow[i], i, blank_id, eos_id);
     gt += (k > prefix); eq += (k == prefix);
   }
   uint32_t total;
@@ -183,11 +200,12 @@ __device__ __noinline__ void select_radix(const float* s_att, int V, int K, int 
   uint32_t gt_before = ex >> 16, eq_before = ex & 0xffffu;
   uint32_t pos = gt_before + min(eq_before, krem);
   for (int i = i0; i < i1; ++i) {
-    uint32_t k = att_key(s_att[i], i, blank_id, eos_id);
+    const float a = arow[i];
+    uint32_t k = att_key(a, i, blank_id, eos_id);
     bool take = (k > prefix) || (k == prefix && eq_before < krem);
     if (k == prefix) ++eq_before;
     if (take && pos < (uint32_t)K) {
-      if (use_lds) out_lds[pos] = i;
+      if (use_lds) { out_lds[pos] = i; out_att_lds[pos] = a; }
       out_g[pos] = i;
       ++pos;
     }
@@ -239,7 +257,23 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
   const int K = p.K, V = p.V;
   const bool smallk = (K <= BLOCK);
 
-  if (p.finished[u] || !p.h_live[cur][grp]) {
+  // publish the count of finished utterances (as of the previous step) where the host can
+  // read it without synchronising: one writer, plain store to device-mapped pinned memory
+  if (grp == 0 && tid == 0) {
+    *(volatile int32_t*)p.host_finished = *p.n_finished;
+    __threadfence_system();
+  }
+
+  // ---------------- first round of loads: g's record and its attention row ----------------
+  // (issued together, before the liveness test, so that they overlap; rows of dead slots are
+  // never dereferenced: their loads are skipped through the uniform early exit below only
+  // after the record arrived, the row loads are issued after it)
+  const int dead = p.finished[u] | (p.h_live[cur][grp] == 0);
+  const int T = p.lens[u];
+  const int tau = p.h_tau[cur][grp], tau_end = p.h_tau_end[cur][grp];
+  const int rs = p.h_rs[cur][grp], re = p.h_re[cur][grp], last = p.h_last[cur][grp];
+  const double off = p.h_off[cur][grp], acum = p.h_att[cur][grp];
+  if (dead) {
     if (tid == 0) {
       p.grp_n[grp] = 0; p.win_s[grp] = 0; p.win_e[grp] = -1; p.stopped[grp] = 0;
       p.ctc_eos[grp] = LOG0D; p.joint_eos[grp] = LOG0D; p.grp_cells[grp] = 0;
@@ -248,7 +282,6 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
   }
 
   TRACE_POINT(p, grp, 0);
-  float* s_att = (float*)(smem + sm.off_att);
   uint32_t* s_work = (uint32_t*)(smem + sm.off_work);
   float* s_F = (float*)(smem + sm.off_f);
   float* s_Fb = s_F + sm.wp_max;
@@ -261,11 +294,18 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
   const float* arow = att + (size_t)grp * V;
   int32_t* g_cid = p.cand_id + (size_t)grp * K;
 
+  // attention row -> registers (restricted mode, rows that fit): PIVOT_NV4 float4 per lane, all
+  // in flight together (clamped, unconditional)
+  const bool in_regs = p.restricted && (V & 3) == 0 && (V >> 2) <= PIVOT_NV4 * BLOCK;
+  float4 arow_r[PIVOT_NV4];
+  if (in_regs) {
+    const float4* a4 = (const float4*)arow;
+    const int nv4 = V >> 2;
+#pragma unroll
+    for (int k = 0; k < PIVOT_NV4; ++k) arow_r[k] = a4[min(tid + k * BLOCK, nv4 - 1)];
+  }
+
   // ---------------- window (needs only g's record) ----------------------------------------
-  const int T = p.lens[u];
-  const int tau = p.h_tau[cur][grp], tau_end = p.h_tau_end[cur][grp];
-  const int rs = p.h_rs[cur][grp], re = p.h_re[cur][grp], last = p.h_last[cur][grp];
-  const double off = p.h_off[cur][grp], acum = p.h_att[cur][grp];
   int s = l > 1 ? l : 1, e = T;
   if (p.win_m1 >= 0) s = max(s, tau - p.win_m1);
   if (p.win_m2 >= 0) e = min(e, tau_end + p.win_m2);
@@ -277,25 +317,7 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
   const float* gb = p.gb[cur] + (size_t)grp * p.Tp;
 
   TRACE_POINT(p, grp, 1);
-  // ---------------- stage the attention row and the f terms (loads overlap) ---------------
-  if (p.restricted) {
-    if ((V & 3) == 0) {                                    // rows are 16-byte aligned: float4, 8 loads in flight
-      const float4* a4 = (const float4*)arow;
-      float4* s4 = (float4*)s_att;
-      const int nv4 = V >> 2;
-      for (int base = 0; base < nv4; base += BLOCK * 8) {
-        // clamped, unconditional loads and stores: all eight loads are in flight together; lanes
-        // past the row's end rewrite its last float4 with the same value
-        float4 r[8];
-#pragma unroll
-        for (int k = 0; k < 8; ++k) r[k] = a4[min(base + tid + k * BLOCK, nv4 - 1)];
-#pragma unroll
-        for (int k = 0; k < 8; ++k) s4[min(base + tid + k * BLOCK, nv4 - 1)] = r[k];
-      }
-    } else {
-      for (int i = tid; i < V; i += BLOCK) s_att[i] = arow[i];
-    }
-  }
+  // ---------------- stage the f terms of the window in LDS ---------------------------------
   for (int i = tid; i < Wp; i += BLOCK) {
     const int t = t0 + i;
     float f = LOG0F, fb = LOG0F;
@@ -308,23 +330,41 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
   const int R = p.eos_run;
   const bool e2 = (p.end_flags & 4) && R > 0 && T >= R && W > 0 && e == T && re == T &&
                   max(s, rs) <= T - R + 1;
-  __syncthreads();
   TRACE_POINT(p, grp, 2);
 
   // ---------------- 1. candidates -----------------------------------------------------------
   if (p.restricted) {
-    const bool ok = select_pivot<BLOCK>(s_att, V, K, p.blank_id, p.eos_id, s_work, (int32_t*)(s_work + PIVOT_CAP),
-                                        s_scan, s_w, smallk, s_cid, g_cid);
-    if (!ok) select_radix<BLOCK>(s_att, V, K, p.blank_id, p.eos_id, s_work, s_scan, s_sel, smallk, s_cid, g_cid);
+    bool ok = false;
+    if (in_regs) {
+      // ids past the row's end, blank and eos never compete: hold them as -inf
+      const int nv4 = V >> 2;
+      const float ninf = -__builtin_huge_valf();
+#pragma unroll
+      for (int k = 0; k < PIVOT_NV4; ++k) {
+        const int i4 = tid + k * BLOCK;
+        if (i4 >= nv4) arow_r[k] = make_float4(ninf, ninf, ninf, ninf);
+        if (i4 == (p.blank_id >> 2) || i4 == (p.eos_id >> 2)) {
+          const int jb = i4 == (p.blank_id >> 2) ? (p.blank_id & 3) : -1;
+          const int je = i4 == (p.eos_id >> 2) ? (p.eos_id & 3) : -1;
+          if (jb == 0 || je == 0) arow_r[k].x = ninf;
+          if (jb == 1 || je == 1) arow_r[k].y = ninf;
+          if (jb == 2 || je == 2) arow_r[k].z = ninf;
+          if (jb == 3 || je == 3) arow_r[k].w = ninf;
+        }
+      }
+      ok = select_pivot<BLOCK>(arow_r, K, p.blank_id, p.eos_id, s_work, (int32_t*)(s_work + PIVOT_CAP),
+                               (int32_t*)(s_work + 2 * PIVOT_CAP), s_scan, s_w, smallk, s_cid, s_av, g_cid);
+    }
+    if (!ok) select_radix<BLOCK>(arow, V, K, p.blank_id, p.eos_id, s_work, s_scan, s_sel, smallk, s_cid, s_av, g_cid);
   } else {
     const int lo_ex = min(p.blank_id, p.eos_id), hi_ex = max(p.blank_id, p.eos_id);
     for (int i = tid; i < K; i += BLOCK) {
       const int id = full_v_id(i, lo_ex, hi_ex);
-      if (smallk) s_cid[i] = id;
+      if (smallk) { s_cid[i] = id; s_av[i] = arow[id]; }
       g_cid[i] = id;
     }
   }
-  __syncthreads();                                         // candidate ids visible to the whole block
+  __syncthreads();                                         // candidates and f terms visible to the whole block
   TRACE_POINT(p, grp, 3);
 
   // ---------------- 3. prefix scores ----------------------------------------------------
@@ -374,12 +414,12 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
       }
       const float inc = (W > 0) ? lse_finish<LPC>(a) : LOG0F;
       if (q == 0) {
-        const float av = p.restricted ? s_att[id] : arow[id];
+        const float av = smallk ? s_av[c] : arow[id];
         const bool valid = inc > LOG0_CLASS;
         const double ctc = valid ? off + (double)inc : LOG0D;
         const double J = valid ? lam * ctc + (1.0 - lam) * (double)av + jbase : LOG0D;
         g_inc[c] = inc; g_catt[c] = av; g_ctc[c] = ctc; g_joint[c] = J;
-        if (smallk) { s_J[c] = (valid && J == J) ? J : LOG0D; s_inc[c] = inc; s_av[c] = av; }
+        if (smallk) { s_J[c] = (valid && J == J) ? J : LOG0D; s_inc[c] = inc; }
       }
       if (e2) {
         const float pre = lse_finish<LPC>(ap);             // running prefix score at frame T-R
@@ -452,7 +492,7 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
   }
 
   if (smallk) {
-    // rank by (joint desc, candidate index asc); candidate index order is token order
+    // rank by (joint desc, token asc)
     if (tid == 0) s_nvalid = 0;
     __syncthreads();                                       // s_J complete
     if (!fire) {
@@ -460,10 +500,11 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
       for (int e0 = 0; e0 < K; e0 += BLOCK / 4) {          // four lanes per candidate
         const int e = e0 + (tid >> 2);
         const double me = e < K ? s_J[e] : LOG0D;
+        const int mtok = e < K ? s_cid[e] : 0x7fffffff;
         int rank = 0;
         for (int c = part; c < K; c += 4) {
           const double o = s_J[c];
-          rank += (o > me) || (o == me && c < e);
+          rank += (o > me) || (o == me && s_cid[c] < mtok);
         }
         rank += __shfl_xor(rank, 1);
         rank += __shfl_xor(rank, 2);
@@ -488,33 +529,35 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
 template <int BLOCK>
 __global__ __launch_bounds__(BLOCK) void k_group_top(Params p, int cur) {
   __shared__ double s_v[BLOCK / 64];
-  __shared__ int s_i[BLOCK / 64];
+  __shared__ int s_i[BLOCK / 64], s_t[BLOCK / 64];
   __shared__ int s_pick[MAX_BEAM];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int grp = blockIdx.x, u = grp / p.Wb, K = p.K;
   if (p.finished[u] || !p.h_live[cur][grp]) return;      // k_score already wrote grp_n = 0
   if (p.stopped[grp]) { if (tid == 0) p.grp_n[grp] = 0; return; }
   const double* J = p.cand_joint + (size_t)grp * K;
+  const int32_t* ids = p.cand_id + (size_t)grp * K;       // equal scores: smaller token id first
   int n = 0;
   for (int r = 0; r < p.Wb; ++r) {
-    double bv = LOG0D; int bi = 0x7fffffff;
+    double bv = LOG0D; int bi = 0x7fffffff, bt = 0x7fffffff;
     for (int c = tid; c < K; c += BLOCK) {
       double v = J[c];
       if (!(v > (double)LOG0_CLASS)) continue;
       bool taken = false;
       for (int k = 0; k < r; ++k) taken |= (s_pick[k] == c);
       if (taken) continue;
-      if (v > bv || (v == bv && c < bi)) { bv = v; bi = c; }
+      const int tk = ids[c];
+      if (v > bv || (v == bv && tk < bt)) { bv = v; bi = c; bt = tk; }
     }
     for (int o = 32; o > 0; o >>= 1) {
-      double ov = __shfl_xor(bv, o); int oi = __shfl_xor(bi, o);
-      if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+      double ov = __shfl_xor(bv, o); int oi = __shfl_xor(bi, o); int ot = __shfl_xor(bt, o);
+      if (ov > bv || (ov == bv && ot < bt)) { bv = ov; bi = oi; bt = ot; }
     }
-    if (lane == 0) { s_v[w] = bv; s_i[w] = bi; }
+    if (lane == 0) { s_v[w] = bv; s_i[w] = bi; s_t[w] = bt; }
     __syncthreads();
     if (tid == 0) {
       for (int k = 1; k < BLOCK / 64; ++k)
-        if (s_v[k] > bv || (s_v[k] == bv && s_i[k] < bi)) { bv = s_v[k]; bi = s_i[k]; }
+        if (s_v[k] > bv || (s_v[k] == bv && s_t[k] < bt)) { bv = s_v[k]; bi = s_i[k]; bt = s_t[k]; }
       s_pick[r] = (bi == 0x7fffffff) ? -1 : bi;
       if (bi != 0x7fffffff) {
         const size_t o = (size_t)grp * p.Wb + r;

@@ -197,6 +197,7 @@ def test_stats_poll_and_done():
     att = np.zeros((3, 3, 200), np.float32)
     rng = np.random.default_rng(0)
     n = 0
+    fin_hist = []
     while True:
         att[:] = rng.normal(size=att.shape).astype(np.float32)
         rc = dec.step(att)
@@ -205,7 +206,11 @@ def test_stats_poll_and_done():
         n += 1
         assert dec.out.step == n
         if n % 2 == 0:
-            assert dec.out.n_finished == int(dec.outputs()["finished"].sum())
+            # a lower bound that lags by at most two poll intervals (here: four steps)
+            assert 0 <= dec.out.n_finished <= int(dec.outputs()["finished"].sum())
+            fin_hist.append(int(dec.outputs()["finished"].sum()))
+            if len(fin_hist) > 3:
+                assert dec.out.n_finished >= fin_hist[-4]
         else:
             assert dec.out.n_finished == -1
         assert n <= 20
@@ -236,7 +241,7 @@ def test_abi_rejects_bad_arguments():
     for bad in (dict(n_utt=0), dict(beam=0), dict(beam=33), dict(vocab=2), dict(blank_id=50),
                 dict(eos_id=0), dict(cand_k=-1), dict(ctc_weight=1.5), dict(t_max=7000),
                 dict(end_flags=8), dict(end_m=9), dict(eos_run=0, end_flags=4),
-                dict(vocab=20000, cand_k=5), dict(max_len_ratio=-1.0)):
+                dict(max_len_ratio=-1.0)):
         rc, h = create(**bad)
         assert rc == m.EINVAL and h is None, bad
     out = ctypes.c_void_p()
