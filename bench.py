@@ -1,8 +1,9 @@
 #!/usr/bin/env python3
 """Throughput of the batched joint CTC/attention beam-search path on one MI355X.
 
-One benchmark "step" is one whole decode of one batch: ctcbs_create (ingest of the CTC
-posteriors) -> ctcbs_step until every utterance has finished -> ctcbs_finalize.  All inputs
+One benchmark "step" is one whole decode of one batch: ingest of the CTC posteriors
+(ctcbs_create for the first batch, ctcbs_reset -- the same work without the allocations -- for
+every later one) -> ctcbs_step until every utterance has finished -> ctcbs_finalize.  All inputs
 are synthetic and already resident in HBM when the timed region starts: the CTC
 log-posteriors come from the device generator, and the attention rows of every step are
 recorded once, in an untimed decode with the same generator keyed by the hypotheses'
@@ -67,6 +68,7 @@ class Batch:
         self.l_cap = int(max(self._cap(int(t)) for t in self.lens))
         self.att = None
         self.n_steps = 0
+        self.h = None
 
     def _cap(self, T):
         w = self.w
@@ -119,7 +121,13 @@ class Batch:
     def decode(self, profile=False):
         """One timed-style decode replaying the recorded rows; returns (result, handle stats)."""
         m, U = self.m, self.U
-        h = m.ctcbs_create(self.cfg, self.d_ctc, self.lens)
+        # one handle serves every decode: the first call allocates, later ones re-initialise it for
+        # the next batch (ctcbs_reset: transposed ingest of the posteriors + empty beams, no allocation)
+        if self.h is None:
+            self.h = m.ctcbs_create(self.cfg, self.d_ctc, self.lens)
+        else:
+            m.ctcbs_reset(self.h, self.d_ctc, self.lens)
+        h = self.h
         out = m.StepOut()
         try:
             if profile:
@@ -133,9 +141,16 @@ class Batch:
                     break
             res = m.ctcbs_finalize(h, U, self.l_cap)
             prof = m.ctcbs_profile_read(h) if profile else None
-        finally:
+        except Exception:
             m.ctcbs_destroy(h)
+            self.h = None
+            raise
         return res, prof
+
+    def close(self):
+        if self.h is not None:
+            self.m.ctcbs_destroy(self.h)
+            self.h = None
 
 
 def cpu_baseline(batch, n_sample):

@@ -121,6 +121,14 @@ int ctcbs_create(const ctcbs_config_t* cfg, const float* d_ctc_logp, const int32
                  ctcbs_t** out);
 
 /*
+ * Algorithm 2's initialisation again, on an existing handle, for the next batch: same
+ * configuration and number of utterances, new posteriors and lengths (each <= t_max).  All
+ * device memory is reused, so an offline run allocates once.  Results of the previous batch
+ * are gone afterwards.  Synchronises the stream.
+ */
+int ctcbs_reset(ctcbs_t* h, const float* d_ctc_logp, const int32_t* h_lens);
+
+/*
  * One iteration of Algorithm 2's loop (Score_Fn with Eq. (1)-(3)/(5), eos split-off, TopB,
  * GatherB, the "p > best_score" test, ENDDETECT) for all utterances.
  * d_att_logp[u][j][k] = log p^a(y^l = k | hypothesis in beam slot j of utterance u) (device,

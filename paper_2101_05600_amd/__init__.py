@@ -26,7 +26,7 @@ HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
 
 EXPORTS = ["ctcbs_create", "ctcbs_step", "ctcbs_poll", "ctcbs_finalize", "ctcbs_stats", "ctcbs_peek",
            "ctcbs_destroy", "ctcbs_strerror", "ctcbs_last_hip_error", "ctcbs_profile",
-           "ctcbs_profile_read"]
+           "ctcbs_profile_read", "ctcbs_reset"]
 
 
 def build():
@@ -66,6 +66,8 @@ def lib():
         vp, i32 = ctypes.c_void_p, ctypes.c_int32
         L.ctcbs_create.restype = i32
         L.ctcbs_create.argtypes = [ctypes.POINTER(Config), vp, vp, ctypes.POINTER(vp)]
+        L.ctcbs_reset.restype = i32
+        L.ctcbs_reset.argtypes = [vp, vp, vp]
         L.ctcbs_step.restype = i32
         L.ctcbs_step.argtypes = [vp, vp, ctypes.POINTER(StepOut)]
         L.ctcbs_poll.restype = i32
@@ -132,6 +134,14 @@ def ctcbs_create(cfg: Config, d_ctc_logp, h_lens):
     if rc != OK:
         raise CtcbsError(rc)
     return out.value
+
+
+def ctcbs_reset(handle, d_ctc_logp, h_lens):
+    """Start the next batch on an existing handle (same configuration, lengths <= t_max)."""
+    lens = np.ascontiguousarray(h_lens, dtype=np.int32)
+    rc = lib().ctcbs_reset(handle, _ptr(d_ctc_logp), lens.ctypes.data_as(ctypes.c_void_p))
+    if rc != OK:
+        raise CtcbsError(rc)
 
 
 def ctcbs_step(handle, d_att_logp, out: StepOut = None):

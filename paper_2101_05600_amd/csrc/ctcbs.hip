@@ -33,6 +33,8 @@ struct ctcbs {
   int32_t step;        // steps enqueued
   int32_t cur;         // buffer holding the current beam
   int32_t l_cap;       // largest step cap over the batch
+  int32_t l_cap_alloc; // step cap of an utterance of t_max frames: what the buffers are sized for
+  int32_t *d_lens, *d_lmax;
   int32_t known_finished;
   size_t score_smem_bytes;
   int score_block, score_lpc, select_block;
@@ -117,6 +119,39 @@ static int validate(const ctcbs_config_t* c) {
   return CTCBS_OK;
 }
 
+// Per-batch part of the initialisation: lengths, step caps, transposed posteriors, empty beams.
+static int ingest(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens) {
+  const ctcbs_config_t& c = h->cfg;
+  Params& p = h->p;
+  const int U = c.n_utt;
+  std::vector<int32_t> lens(h_lens, h_lens + U), lmax(U);
+  int l_cap = 1;
+  for (int u = 0; u < U; ++u) {
+    if (lens[u] < 1 || lens[u] > c.t_max) return CTCBS_EINVAL;
+    lmax[u] = step_cap(&c, lens[u]);
+    if (lmax[u] > l_cap) l_cap = lmax[u];
+  }
+  hipStream_t st = h->stream;
+  HIPCHK(hipStreamSynchronize(st));              // the staging vectors below are reused
+  h->lens.swap(lens); h->lmax.swap(lmax); h->l_cap = l_cap;
+  const size_t UW = (size_t)U * p.Wb;
+  HIPCHK(hipMemcpyAsync(h->d_lens, h->lens.data(), sizeof(int32_t) * U, hipMemcpyHostToDevice, st));
+  HIPCHK(hipMemcpyAsync(h->d_lmax, h->lmax.data(), sizeof(int32_t) * U, hipMemcpyHostToDevice, st));
+  HIPCHK(hipMemsetAsync(p.grp_n, 0, sizeof(int32_t) * UW, st));
+  HIPCHK(hipMemsetAsync(p.stopped, 0, sizeof(int32_t) * UW, st));
+  dim3 tg((p.V + 63) / 64, (c.t_max + 4 + 63) / 64, U);
+  hipLaunchKernelGGL(k_transpose, tg, dim3(256), 0, st, p, d_ctc_logp);
+  HIPCHK(hipGetLastError());
+  hipLaunchKernelGGL(k_init_state, dim3(U), dim3(64), 0, st, p);
+  HIPCHK(hipGetLastError());
+  h->step = 0; h->cur = 0; h->known_finished = 0;
+  h->profiling = false; h->ev_used = 0;
+  h->throttle_k = 0; h->throttle_armed[0] = h->throttle_armed[1] = false;
+  *h->h_flag = 0;
+  HIPCHK(hipStreamSynchronize(st));
+  return CTCBS_OK;
+}
+
 static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens) {
   const ctcbs_config_t& c = h->cfg;
   Params& p = h->p;
@@ -132,19 +167,14 @@ static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens)
   p.end_c = c.end_c; p.eos_run = c.eos_run; p.end_d = c.end_d;
   p.lambda = (double)c.ctc_weight; p.beta = (double)c.length_bonus;
 
-  h->lens.assign(h_lens, h_lens + U);
-  h->lmax.resize(U);
-  h->l_cap = 1;
-  for (int u = 0; u < U; ++u) {
-    if (h->lens[u] < 1 || h->lens[u] > c.t_max) return CTCBS_EINVAL;
-    h->lmax[u] = step_cap(&c, h->lens[u]);
-    if (h->lmax[u] > h->l_cap) h->l_cap = h->lmax[u];
-  }
-  p.l_cap = h->l_cap;
+  // capacity for any batch of lengths <= t_max (the step cap grows with the length)
+  h->l_cap_alloc = step_cap(&c, c.t_max);
+  h->l_cap = h->l_cap_alloc;
+  p.l_cap = h->l_cap_alloc;
 
   const size_t UW = (size_t)U * Wb;
   int rc;
-  int32_t *d_lens, *d_lmax;
+  int32_t*& d_lens = h->d_lens; int32_t*& d_lmax = h->d_lmax;
 #define A(ptr, n) if ((rc = dev_alloc(h, &(ptr), (n))) != CTCBS_OK) return rc
   A(p.xT, (size_t)U * V * p.Tp);
   A(d_lens, (size_t)U); A(d_lmax, (size_t)U);
@@ -163,14 +193,14 @@ static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens)
   A(p.ctc_eos, UW); A(p.joint_eos, UW); A(p.stopped, UW); A(p.grp_cells, UW);
   A(p.utt, (size_t)U); A(p.finished, (size_t)U); A(p.cells, (size_t)U); A(p.groups, (size_t)U);
   A(p.n_finished, (size_t)1);
-  const size_t trie_n = (size_t)(h->l_cap + 1) * UW;
+  const size_t trie_n = (size_t)(h->l_cap_alloc + 1) * UW;
   A(p.trie_parent, trie_n); A(p.trie_token, trie_n); A(p.trie_tau, trie_n);
   A(p.out_parent, UW); A(p.out_token, UW); A(p.out_score, UW); A(p.out_live, UW);
   A(p.out_tau, UW); A(p.out_tau_end, UW); A(p.out_eos_added, UW); A(p.out_stopped, UW);
 #ifdef CTCBS_TRACE
   A(p.trace, UW * 16);
 #endif
-  h->res_cap = h->l_cap;
+  h->res_cap = h->l_cap_alloc;
   A(h->d_tokens, (size_t)U * h->res_cap); A(h->d_frames, (size_t)U * h->res_cap);
   A(h->d_ntok, (size_t)U); A(h->d_flags, (size_t)U); A(h->d_score, (size_t)U);
 #undef A
@@ -188,18 +218,6 @@ static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens)
     HIPCHK(hipEventCreateWithFlags(&h->throttle[1], hipEventDisableTiming));
     h->throttle_made = true;
   }
-  hipStream_t st = h->stream;
-  HIPCHK(hipMemcpyAsync(d_lens, h->lens.data(), sizeof(int32_t) * U, hipMemcpyHostToDevice, st));
-  HIPCHK(hipMemcpyAsync(d_lmax, h->lmax.data(), sizeof(int32_t) * U, hipMemcpyHostToDevice, st));
-  HIPCHK(hipMemsetAsync(p.grp_n, 0, sizeof(int32_t) * UW, st));
-  HIPCHK(hipMemsetAsync(p.stopped, 0, sizeof(int32_t) * UW, st));
-
-  dim3 tg((V + 63) / 64, (c.t_max + 4 + 63) / 64, U);
-  hipLaunchKernelGGL(k_transpose, tg, dim3(256), 0, st, p, d_ctc_logp);
-  HIPCHK(hipGetLastError());
-  hipLaunchKernelGGL(k_init_state, dim3(U), dim3(64), 0, st, p);
-  HIPCHK(hipGetLastError());
-
   // launch shapes of the per-step kernels
   h->score_block = 256;
   const bool windowed = c.win_m1 >= 0 && c.win_m2 >= 0 && (c.win_m1 + c.win_m2) <= 448;
@@ -218,11 +236,7 @@ static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens)
   int nw = Wb < 16 ? Wb : 16;
   h->select_block = 64 * (nw <= 4 ? 4 : (nw <= 8 ? 8 : 16));
 
-  h->step = 0; h->cur = 0; h->known_finished = 0;
-  h->profiling = false; h->ev_used = 0;
-  h->throttle_k = 0; h->throttle_armed[0] = h->throttle_armed[1] = false;
-  HIPCHK(hipStreamSynchronize(st));
-  return CTCBS_OK;
+  return ingest(h, d_ctc_logp, h_lens);
 }
 
 extern "C" int ctcbs_create(const ctcbs_config_t* cfg, const float* d_ctc_logp, const int32_t* h_lens,
@@ -304,6 +318,11 @@ extern "C" int ctcbs_step(ctcbs_t* h, const float* d_att_logp, ctcbs_step_out_t*
   return CTCBS_OK;
 }
 
+extern "C" int ctcbs_reset(ctcbs_t* h, const float* d_ctc_logp, const int32_t* h_lens) {
+  if (!h || !d_ctc_logp || !h_lens) return CTCBS_EINVAL;
+  return ingest(h, d_ctc_logp, h_lens);
+}
+
 extern "C" int ctcbs_poll(ctcbs_t* h, int32_t* n_finished) {
   if (!h) return CTCBS_EINVAL;
   int32_t v = 0;
@@ -318,7 +337,7 @@ extern "C" int ctcbs_finalize(ctcbs_t* h, int32_t* h_tokens, int32_t cap, int32_
                               int32_t* h_frames, int32_t* h_flags) {
   if (!h || !h_tokens || !h_ntok || !h_score || cap < 0) return CTCBS_EINVAL;
   const int U = h->p.U, rc_cap = h->res_cap;
-  const size_t fin_lds = (size_t)(h->l_cap + 1) * h->p.Wb + (size_t)h->l_cap + 1;
+  const size_t fin_lds = (size_t)(h->l_cap_alloc + 1) * h->p.Wb + (size_t)h->l_cap_alloc + 1;
   const int use_lds = fin_lds <= 60 * 1024;
   hipLaunchKernelGGL((k_finalize<256>), dim3(U), dim3(256), use_lds ? fin_lds : 0, h->stream, h->p, h->cur,
                      h->step, rc_cap, use_lds, h->d_tokens, h->d_frames, h->d_ntok, h->d_score, h->d_flags);
@@ -360,7 +379,7 @@ extern "C" int ctcbs_stats(ctcbs_t* h, uint64_t* cells, uint64_t* groups, int32_
 extern "C" int ctcbs_profile(ctcbs_t* h, int32_t enable) {
   if (!h) return CTCBS_EINVAL;
   if (enable && h->events.empty()) {
-    h->events.resize((size_t)3 * (h->l_cap + 1));
+    h->events.resize((size_t)3 * (h->l_cap_alloc + 1));
     for (size_t i = 0; i < h->events.size(); ++i) {
       hipError_t e = hipEventCreate(&h->events[i]);
       if (e != hipSuccess) {

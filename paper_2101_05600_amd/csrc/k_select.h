@@ -67,14 +67,13 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
   __shared__ double s_J[MAXE];
   __shared__ int s_par[MAXE], s_ci[MAXE], s_tok[MAXE];
   __shared__ float s_inc[MAXE], s_att[MAXE];
-  __shared__ int s_base[MAX_BEAM + 1];
   __shared__ int s_sel[MAX_BEAM];          // entry index of the new beam's slot n
   // old slots' records
   __shared__ int o_live[MAX_BEAM], o_n[MAX_BEAM], o_stp[MAX_BEAM], o_tau[MAX_BEAM], o_tau_end[MAX_BEAM];
   __shared__ int o_rs[MAX_BEAM], o_re[MAX_BEAM], o_last[MAX_BEAM], o_ws[MAX_BEAM], o_we[MAX_BEAM];
   __shared__ long long o_cells[MAX_BEAM];
   __shared__ double o_je[MAX_BEAM], o_hatt[MAX_BEAM], o_off[MAX_BEAM];
-  __shared__ int s_nnew, s_fin;
+  __shared__ int s_fin;
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int u = blockIdx.x, Wb = p.Wb;
@@ -117,20 +116,25 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
   if (tid < MAX_BEAM) s_sel[tid] = -1;
   __syncthreads();
   TRACE_POINT(p, u, 9);
-  if (tid == 0) {
-    int acc = 0;
-    for (int j = 0; j < Wb; ++j) { s_base[j] = acc; acc += o_n[j]; }
-    s_base[Wb] = acc;
+  // every thread sums the list lengths itself (independent LDS reads, no serial section)
+  int ne = 0;
+  int base_of[EPT];
+#pragma unroll
+  for (int k = 0; k < EPT; ++k) base_of[k] = 0;
+#pragma unroll 8
+  for (int j = 0; j < Wb; ++j) {
+    const int nj = o_n[j];
+#pragma unroll
+    for (int k = 0; k < EPT; ++k) base_of[k] += (j < (tid + k * BLOCK) / Wb) ? nj : 0;
+    ne += nj;
   }
-  __syncthreads();
-  const int ne = s_base[Wb];
 #pragma unroll
   for (int k = 0; k < EPT; ++k) {
     const int i = tid + k * BLOCK;
     if (i < Wb * Wb) {
       const int j = i / Wb, r = i % Wb;
       if (r < o_n[j]) {
-        const int e = s_base[j] + r;
+        const int e = base_of[k] + r;
         s_J[e] = eJ[k]; s_par[e] = j; s_ci[e] = eci[k]; s_tok[e] = etok[k];
         s_inc[e] = einc[k]; s_att[e] = eatt[k];
       }
@@ -144,11 +148,14 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
     const bool have = e < ne;
     const double me = have ? s_J[e] : LOG0D;
     // equal scores: entries are stored in (parent slot, token) order, so the position decides
-    int rank = 0;
-    for (int o = part; o < ne; o += 8) {
+    int rank = 0, rank2 = 0;
+    for (int o = part; o < ne; o += 16) {                  // two independent chains of LDS reads
       const double v = s_J[o];
+      const double v2 = o + 8 < ne ? s_J[o + 8] : -1.0e300;
       rank += (v > me) || (v == me && o < e);
+      rank2 += (v2 > me) || (v2 == me && o + 8 < e);
     }
+    rank += rank2;
     rank += __shfl_xor(rank, 1);
     rank += __shfl_xor(rank, 2);
     rank += __shfl_xor(rank, 4);
@@ -158,8 +165,8 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
 
   TRACE_POINT(p, u, 10);
   // ---- ended set, end detection: wave 0, lane j = old slot j ---------------------------------
+  const int n_new = min(ne, Wb);
   if (w == 0) {
-    const int n_new = min(ne, Wb);
     const bool has_best = ne > 0;
     const double best = has_best ? s_J[s_sel[0]] : LOG0D;
     const bool forced = (l >= lmax_u);
@@ -212,42 +219,19 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
       }
       p.cells[u] += (unsigned long long)cells;
       p.groups[u] += (unsigned long long)ngroups;
-      s_nnew = n_new; s_fin = fin ? 1 : 0;
+      s_fin = fin ? 1 : 0;
     }
   }
-  __syncthreads();
-  const int n_new = s_nnew;
-  const bool fin = s_fin != 0;
   TRACE_POINT(p, u, 11);
-
-  // ---- new beam: records, outputs, back-pointers ------------------------------------------
-  const size_t trie_l = ((size_t)l * p.U + u) * Wb;
-  for (int n = tid; n < Wb; n += BLOCK) {
-    const size_t h = h0 + n;
-    if (n < n_new) {
-      const int e = s_sel[n], par = s_par[e], tok = s_tok[e];
-      p.out_parent[h] = par; p.out_token[h] = tok; p.out_score[h] = (float)s_J[e];
-      p.out_live[h] = fin ? 0 : 1;
-      p.trie_parent[trie_l + n] = par; p.trie_token[trie_l + n] = tok;
-      p.h_live[nxt][h] = fin ? 0 : 1;
-      p.h_last[nxt][h] = tok;
-      p.h_rs[nxt][h] = o_ws[par]; p.h_re[nxt][h] = o_we[par];
-      p.h_off[nxt][h] = o_off[par] + (double)s_inc[e];
-      p.h_att[nxt][h] = o_hatt[par] + (double)s_att[e];
-      p.h_joint[nxt][h] = s_J[e];
-    } else {
-      p.out_parent[h] = -1; p.out_token[h] = -1; p.out_score[h] = LOG0F; p.out_live[h] = 0;
-      p.out_tau[h] = 0; p.out_tau_end[h] = 0;
-      p.trie_parent[trie_l + n] = -1; p.trie_token[trie_l + n] = -1; p.trie_tau[trie_l + n] = 0;
-      p.h_live[nxt][h] = 0;
-    }
-  }
 
   TRACE_POINT(p, u, 12);
   // ---- forward variables of the new hypotheses --------------------------------------------
   const float* xu = p.xT + (size_t)u * p.V * p.Tp;
   const float* x0 = xu + (size_t)p.blank_id * p.Tp;
-  for (int n = w; n < n_new && !fin; n += NW) {
+  // (wave 0 is busy with the ended set above; the other waves take the survivors at once.  A
+  // finished utterance's new state is computed too but never used: its slots are marked dead.)
+  const size_t trie_l = ((size_t)l * p.U + u) * Wb;
+  for (int n = w - 1; n >= 0 && n < n_new; n += NW - 1) {
     const int e = s_sel[n], par = s_par[e], tok = s_tok[e];
     const size_t hp = h0 + par;
     const float inc = s_inc[e];
@@ -317,5 +301,28 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
     }
   }
   __syncthreads();
+  const bool fin = s_fin != 0;
+  // ---- new beam: records, outputs, back-pointers ------------------------------------------
+  for (int n = tid; n < Wb; n += BLOCK) {
+    const size_t h = h0 + n;
+    if (n < n_new) {
+      const int e = s_sel[n], par = s_par[e], tok = s_tok[e];
+      p.out_parent[h] = par; p.out_token[h] = tok; p.out_score[h] = (float)s_J[e];
+      p.out_live[h] = fin ? 0 : 1;
+      p.trie_parent[trie_l + n] = par; p.trie_token[trie_l + n] = tok;
+      p.h_live[nxt][h] = fin ? 0 : 1;
+      p.h_last[nxt][h] = tok;
+      p.h_rs[nxt][h] = o_ws[par]; p.h_re[nxt][h] = o_we[par];
+      p.h_off[nxt][h] = o_off[par] + (double)s_inc[e];
+      p.h_att[nxt][h] = o_hatt[par] + (double)s_att[e];
+      p.h_joint[nxt][h] = s_J[e];
+    } else {
+      p.out_parent[h] = -1; p.out_token[h] = -1; p.out_score[h] = LOG0F; p.out_live[h] = 0;
+      p.out_tau[h] = 0; p.out_tau_end[h] = 0;
+      p.trie_parent[trie_l + n] = -1; p.trie_token[trie_l + n] = -1; p.trie_tau[trie_l + n] = 0;
+      p.h_live[nxt][h] = 0;
+    }
+  }
+
   TRACE_POINT(p, u, 13);
 }

@@ -222,6 +222,70 @@ def test_stats_poll_and_done():
     dec.close()
 
 
+def test_reset_reuses_a_handle_for_the_next_batch():
+    """Decoding batch B on a handle that already decoded batch A equals decoding B on a fresh handle."""
+    wa = small("cfg1", n_utt=3, t_lo=40, t_hi=120, vocab=400, beam=4, cand_k=12, win_m1=20, win_m2=20,
+               end_flags=7, eos_run=5)
+    lens_a, ctc_a = make_inputs(wa)
+    wb = dict(wa); wb["seed"] = wa["seed"] + 1
+    lens_b = gen.workload_lengths(wb)
+    ctc_b = gen.workload_ctc(wb, lens_b)
+    t_max = max(ctc_a.shape[1], ctc_b.shape[1])
+
+    def pad(c):
+        out = np.full((c.shape[0], t_max, c.shape[2]), np.nan, np.float32)
+        out[:, :c.shape[1]] = c
+        return out
+
+    def run(dec, w, lens):
+        U, Wb, V = len(lens), w["beam"], w["vocab"]
+        basis = gen.prefix_hash([])
+        hashes = [[basis] * Wb for _ in range(U)]
+        live = np.zeros((U, Wb), bool); live[:, 0] = True
+        step, trace = 0, []
+        while True:
+            step += 1
+            att = host_att(w, step, hashes, live, U)
+            if dec.step(att) == dec.m.DONE:
+                break
+            out = dec.outputs()
+            trace.append((out["parent"].copy(), out["token"].copy(), out["score"].copy()))
+            nh = [[basis] * Wb for _ in range(U)]
+            for i in range(U):
+                for n in range(Wb):
+                    if out["live"][i, n]:
+                        nh[i][n] = gen.prefix_hash_extend(hashes[i][out["parent"][i, n]], out["token"][i, n])
+            hashes, live = nh, out["live"].astype(bool)
+            if out["finished"].all():
+                break
+        return trace, dec.finalize(frames=True)
+
+    import torch
+    dec = GpuDecoder(wa, pad(ctc_a), lens_a)
+    run(dec, wa, lens_a)
+    d_b = torch.from_numpy(pad(ctc_b)).cuda()
+    dec.m.ctcbs_reset(dec.h, d_b, lens_b)
+    dec.lens = np.asarray(lens_b, np.int32)
+    tr1, r1 = run(dec, wb, lens_b)
+    dec.close()
+    fresh = GpuDecoder(wb, pad(ctc_b), lens_b)
+    tr2, r2 = run(fresh, wb, lens_b)
+    fresh.close()
+    assert len(tr1) == len(tr2)
+    for a, b in zip(tr1, tr2):
+        for x, y in zip(a, b):
+            assert np.array_equal(x, y)
+    for x, y in zip(r1, r2):
+        assert np.array_equal(x, y)
+    # a length beyond t_max is refused and leaves the handle usable
+    bad = GpuDecoder(wa, pad(ctc_a), lens_a)
+    import ctypes
+    too_long = np.array([t_max + 1] * 3, np.int32)
+    assert bad.m.lib().ctcbs_reset(bad.h, d_b.data_ptr(), too_long.ctypes.data_as(ctypes.c_void_p)) == bad.m.EINVAL
+    run(bad, wa, lens_a)
+    bad.close()
+
+
 def test_abi_rejects_bad_arguments():
     import ctypes
     import torch
