@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--poll-every", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=24, help="utterances in the oracle's timed sample")
+    ap.add_argument("--inflight", type=int, default=1,
+                    help="batches decoded concurrently, each on its own handle and stream (offline decoding "
+                         "always has more batches queued); the default 1 is the headline figure")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (known traffic, for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -151,6 +154,37 @@ class Batch:
         if self.h is not None:
             self.m.ctcbs_destroy(self.h)
             self.h = None
+        for h in getattr(self, "hs", []):
+            self.m.ctcbs_destroy(h)
+        self.hs = []
+
+    def decode_many(self, n):
+        """n decodes of the same batch in flight at once, one handle and one stream each, their steps
+        enqueued round-robin by this one host thread."""
+        m, torch, U = self.m, self.torch, self.U
+        if not getattr(self, "hs", None):
+            self.streams = [torch.cuda.Stream() for _ in range(n)]
+            self.hs = []
+            for st in self.streams:
+                cfg = m.make_config(n_utt=self.U, t_max=self.t_max, poll_every=self.poll_every,
+                                    stream=st.cuda_stream,
+                                    **{k: v for k, v in self.w.items() if k not in ("n_utt", "stream")})
+                self.hs.append(m.ctcbs_create(cfg, self.d_ctc, self.lens))
+        else:
+            for h in self.hs:
+                m.ctcbs_reset(h, self.d_ctc, self.lens)
+        outs = [m.StepOut() for _ in self.hs]
+        live = [True] * len(self.hs)
+        for step in range(1, self.l_cap + 1):
+            for i, h in enumerate(self.hs):
+                if not live[i]:
+                    continue
+                if m.ctcbs_step(h, self.att_ptr[min(step, self.n_steps) - 1], outs[i]) == m.DONE or \
+                        outs[i].n_finished == U:
+                    live[i] = False
+            if not any(live):
+                break
+        return [m.ctcbs_finalize(h, U, self.l_cap) for h in self.hs]
 
 
 def cpu_baseline(batch, n_sample):
@@ -232,14 +266,28 @@ def main():
         dst.copy_(src)                       # reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
         del src, dst
-    for _ in range(a.warmup):
-        b.decode()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(a.steps):
-        res, _ = b.decode()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    if a.inflight > 1:
+        for _ in range(a.warmup):
+            b.decode_many(a.inflight)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(a.steps):
+            many = b.decode_many(a.inflight)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / a.inflight      # per decoded batch
+        res = many[-1]
+        for r in many:
+            for x, y in zip(r[:3], ref[:3]):
+                assert np.array_equal(x, y), "a concurrent decode did not reproduce the recorded decode"
+    else:
+        for _ in range(a.warmup):
+            b.decode()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(a.steps):
+            res, _ = b.decode()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
     for x, y in zip(res[:3], ref[:3]):
         assert np.array_equal(x, y), "timed decode did not reproduce the recorded decode"
     ms = dt / a.steps * 1e3
@@ -272,7 +320,7 @@ def main():
                                f"M2={w['win_m2']}, end_flags={w['end_flags']}; one step = one whole "
                                f"batch decode (create + {b.n_steps} beam-search steps + finalize)",
                    "decode_steps": b.n_steps, "cells_per_decode": b.cells,
-                   "poll_every": a.poll_every},
+                   "poll_every": a.poll_every, "batches_in_flight": a.inflight},
         "roofline": {"bound": "hbm", "kernel": "k_score", "achieved": ach, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": traffic,
                      "avg_launch_us": score_ms * 1e3 / max(n_prof, 1),

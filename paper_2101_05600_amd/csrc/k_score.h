@@ -316,6 +316,13 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
   const float* gn = p.gn[cur] + (size_t)grp * p.Tp;
   const float* gb = p.gb[cur] + (size_t)grp * p.Tp;
 
+  // eos inputs (thread 0), fetched now so that the epilogue does not wait for them
+  float eos_n = LOG0F, eos_b = LOG0F, eos_a = 0.0f;
+  if (tid == 0) {
+    if (rs <= T && re >= T) { eos_n = gn[T]; eos_b = gb[T]; }
+    eos_a = arow[p.eos_id];
+  }
+
   TRACE_POINT(p, grp, 1);
   // ---------------- stage the f terms of the window in LDS ---------------------------------
   for (int i = tid; i < Wp; i += BLOCK) {
@@ -431,12 +438,11 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
   TRACE_POINT(p, grp, 4);
   // ---------------- 4. eos, eos-run rule, group list -------------------------------------
   if (tid == 0) {
-    float ce = LOG0F;
-    if (rs <= T && re >= T) ce = canon0(lae(gn[T], gb[T]));
+    const float ce = (rs <= T && re >= T) ? canon0(lae(eos_n, eos_b)) : LOG0F;
     const bool v = ce > LOG0_CLASS;
     const double ctc = v ? off + (double)ce : LOG0D;
     p.ctc_eos[grp] = ctc;
-    p.joint_eos[grp] = v ? lam * ctc + (1.0 - lam) * (double)arow[p.eos_id] + jbase : LOG0D;
+    p.joint_eos[grp] = v ? lam * ctc + (1.0 - lam) * (double)eos_a + jbase : LOG0D;
     p.win_s[grp] = s; p.win_e[grp] = e;
     p.grp_cells[grp] = (long long)K * (long long)W;
   }
