@@ -248,7 +248,7 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
   __shared__ uint32_t s_scan[BLOCK / 64 + 1];
   __shared__ uint32_t s_w[BLOCK / 64];
   __shared__ uint32_t s_sel[2];
-  __shared__ float s_e2w[(BLOCK / 64) * MAX_EOS_RUN];
+  __shared__ float s_e2w[(BLOCK / 64) * MAX_EOS_RUN + 1];
   __shared__ int s_nvalid;
 
   const int tid = threadIdx.x;
@@ -403,22 +403,12 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
       const float4* col = (const float4*)(xu + (size_t)id * p.Tp + t0);
       const float4* f4 = (const float4*)(s_F + ((id == last) ? sm.wp_max : 0));   // Fb follows F
       Lse a; a.m = LOG0F; a.s = 0.0f;
-      Lse ap = a;                                          // eos-run rule: the sum without the last R frames
-      const int t_cut = T - R;
 #pragma unroll
       for (int it = 0; it < IT; ++it) {
         const int i = q + it * LPC;
-        if (i < n4) {
-          const float4 f = f4[i];
-          lse_add4(a, x[b][it], f);
-          if (e2) lse_add4_upto(ap, x[b][it], f, t0 + 4 * i, t_cut);
-        }
+        if (i < n4) lse_add4(a, x[b][it], f4[i]);
       }
-      for (int i = q + IT * LPC; i < n4; i += LPC) {
-        const float4 xv = col[i], f = f4[i];
-        lse_add4(a, xv, f);
-        if (e2) lse_add4_upto(ap, xv, f, t0 + 4 * i, t_cut);
-      }
+      for (int i = q + IT * LPC; i < n4; i += LPC) lse_add4(a, col[i], f4[i]);
       const float inc = (W > 0) ? lse_finish<LPC>(a) : LOG0F;
       if (q == 0) {
         const float av = smallk ? s_av[c] : arow[id];
@@ -427,10 +417,6 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
         const double J = valid ? lam * ctc + (1.0 - lam) * (double)av + jbase : LOG0D;
         g_inc[c] = inc; g_catt[c] = av; g_ctc[c] = ctc; g_joint[c] = J;
         if (smallk) { s_J[c] = (valid && J == J) ? J : LOG0D; s_inc[c] = inc; }
-      }
-      if (e2) {
-        const float pre = lse_finish<LPC>(ap);             // running prefix score at frame T-R
-        if (q == 0) p.cand_pre[(size_t)grp * K + c] = pre;
       }
     }
   }
@@ -448,6 +434,35 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
   }
   int fire = 0;
   if (e2) {
+    // Frame T is one of the R frames and there X_T is simply the best full prefix score of the
+    // extensions, which is already known: most eligible hypotheses fail this test and skip the rest.
+    __syncthreads();                                       // s_inc / g_inc of all candidates written
+    float xt = -3.0e38f;
+    for (int c = tid; c < K; c += BLOCK) xt = fmaxf(xt, canon0(smallk ? s_inc[c] : g_inc[c]));
+    xt = row16_max(xt);
+    xt = fmaxf(fmaxf(lane_f(xt, 0), lane_f(xt, 16)), fmaxf(lane_f(xt, 32), lane_f(xt, 48)));
+    if ((tid & 63) == 0) s_e2w[tid >> 6] = xt;
+    if (tid == 0) s_e2w[BLOCK / 64] = (rs <= T && re >= T) ? canon0(lae(eos_n, eos_b)) : LOG0F;
+    __syncthreads();
+    float XT = s_e2w[0];
+#pragma unroll
+    for (int w2 = 1; w2 < BLOCK / 64; ++w2) XT = fmaxf(XT, s_e2w[w2]);
+    const float ET = s_e2w[BLOCK / 64];
+    const bool maybe = (ET > LOG0_CLASS) && (XT < LOG0_CLASS || ET > XT);
+    __syncthreads();                                       // s_e2w is reused below
+    if (maybe) {
+    // running prefix score of every extension at frame T-R: the same sum with the last R frames
+    // cut off (second pass over the columns; they are still in cache)
+    const int t_cut = T - R;
+    for (int c = sg; c < K; c += NSG) {
+      const int id = smallk ? s_cid[c] : g_cid[c];
+      const float4* col = (const float4*)(xu + (size_t)id * p.Tp + t0);
+      const float4* f4 = (const float4*)(s_F + ((id == last) ? sm.wp_max : 0));
+      Lse ap; ap.m = LOG0F; ap.s = 0.0f;
+      for (int i = q; i < n4; i += LPC) lse_add4_upto(ap, col[i], f4[i], t0 + 4 * i, t_cut);
+      const float pre = lse_finish<LPC>(ap);
+      if (q == 0) p.cand_pre[(size_t)grp * K + c] = pre;
+    }
     __syncthreads();                                       // cand_pre written by this block
     float xmax[MAX_EOS_RUN];                               // per frame: best running prefix score seen by this lane
 #pragma unroll
@@ -491,6 +506,7 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
     }
     __syncthreads();
     fire = s_nvalid;
+    }                                                      // maybe
     if (tid == 0) p.stopped[grp] = fire;
     __syncthreads();                                       // s_nvalid is reset below
   } else if (tid == 0) {
