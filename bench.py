@@ -36,6 +36,7 @@ def parse():
     ap.add_argument("--poll-every", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=24, help="utterances in the oracle's timed sample")
+    ap.add_argument("--utts", type=int, default=0, help="override the workload's utterances per batch")
     ap.add_argument("--inflight", type=int, default=1,
                     help="batches decoded concurrently, each on its own handle and stream (offline decoding "
                          "always has more batches queued); the default 1 is the headline figure")
@@ -257,6 +258,8 @@ def main():
         sys.exit(2)
     m.lib()
     w = gen.workload(a.workload)
+    if a.utts > 0:
+        w["n_utt"] = a.utts
     b = Batch(w, a.poll_every)
     ref = b.record()
     if a.calib_copy:

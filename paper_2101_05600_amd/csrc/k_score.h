@@ -25,7 +25,7 @@
 
 struct ScoreSmem {
   // byte offsets into dynamic LDS, computed on the host
-  int32_t off_work;   // union: uint32 hist[1 << RADIX_BITS] | { uint32 key[CAP]; int32 idx[CAP]; int32 flag[CAP] }
+  int32_t off_work;   // union: uint32 hist[1 << RADIX_BITS] | { uint32 key[CAP + 4]; int32 idx[CAP + 4] }
   int32_t off_f;      // float F[wp_max], Fb[wp_max]
   int32_t off_small;  // double J[Ks]; int32 cand_id[Ks]; float inc[Ks], att[Ks]  (Ks = K if K <= BLOCK else 0)
   int32_t wp_max;     // floats available per F array
@@ -41,12 +41,11 @@ __device__ __forceinline__ float key_to_att(uint32_t k) {
 // themselves; only each lane's maximum and the few collected values are turned into
 // order-preserving keys.  Returns false (uniformly) if the short list would overflow or, with
 // NaNs in the row, would hold fewer than K values.  Writes the K ids (and their attention
-// values) in short-list order.
+// values) best first.
 template <int BLOCK>
 __device__ __forceinline__ bool select_pivot(const float4 (&v)[PIVOT_NV4], int K, int blank_id, int eos_id,
-                                             uint32_t* s_key, int32_t* s_idx, int32_t* s_flag,
-                                             uint32_t* s_scan, uint32_t* s_w, bool use_lds, int32_t* out_lds,
-                                             float* out_att_lds, int32_t* out_g) {
+                                             uint32_t* s_key, int32_t* s_idx, uint32_t* s_w, bool use_lds,
+                                             int32_t* out_lds, float* out_att_lds, int32_t* out_g) {
   constexpr int NW = BLOCK / 64;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const float ninf = -__builtin_huge_valf();
@@ -71,33 +70,49 @@ __device__ __forceinline__ bool select_pivot(const float4 (&v)[PIVOT_NV4], int K
   for (int i = 1; i < NW; ++i) Lk = min(Lk, s_w[i]);
   // at least NW * r >= K values are >= L (as a float: -inf if no wave had r finite maxima)
   const float L = Lk <= att_key(ninf, -1, -2, -2) ? ninf : key_to_att(Lk);
-  uint32_t cnt = 0;
+  // hits are rare (about 1.4 K of the whole row): per (k, j) slot one ballot says whether any
+  // lane of the wave holds one; empty slots cost a compare and a scalar test
+  int wave_total = 0;
 #pragma unroll
   for (int k = 0; k < PIVOT_NV4; ++k)
-    cnt += (v[k].x >= L) + (v[k].y >= L) + (v[k].z >= L) + (v[k].w >= L);
-  uint32_t total;
-  uint32_t pos = block_excl_scan_u32<BLOCK>(cnt, s_scan, &total);
-  if (total > PIVOT_CAP || total < (uint32_t)K) return false;
-  if (cnt) {
+    wave_total += __popcll(__ballot(v[k].x >= L)) + __popcll(__ballot(v[k].y >= L)) +
+                  __popcll(__ballot(v[k].z >= L)) + __popcll(__ballot(v[k].w >= L));
+  __syncthreads();                                         // s_w was read by everyone
+  if (lane == 0) s_w[w] = (uint32_t)wave_total;
+  __syncthreads();
+  int base = 0, total = 0;
 #pragma unroll
-    for (int k = 0; k < PIVOT_NV4; ++k) {
-      const float e[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
+  for (int i = 0; i < NW; ++i) { const int c = (int)s_w[i]; base += i < w ? c : 0; total += c; }
+  if (total > PIVOT_CAP || total < K) return false;
+  const bool linf = (L == ninf);                           // then excluded ids (held as -inf) are hits too
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        if (e[j] >= L) {
+  for (int k = 0; k < PIVOT_NV4; ++k) {
+    const float e[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const bool mine = e[j] >= L;
+      const unsigned long long m = __ballot(mine);
+      if (m != 0ull) {                                     // uniform over the wave
+        if (mine) {
           const int id = 4 * (tid + k * BLOCK) + j;
-          s_key[pos] = att_key(e[j], id, blank_id, eos_id);     // excluded ids (held as -inf) rank last
+          const int pos = base + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
+                                        __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+          const uint32_t u = __float_as_uint(e[j]);
+          uint32_t key = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+          if (linf && (id == blank_id || id == eos_id)) key = 0u;   // below a genuine -inf
+          s_key[pos] = key;
           s_idx[pos] = id;
-          ++pos;
         }
+        base += __popcll(m);
+      }
     }
   }
-  const int n = (int)total;
+  const int n = total;
   const int n4 = (n + 3) >> 2;
   if (tid < 4 && n + tid < 4 * n4) { s_key[n + tid] = 0u; s_idx[n + tid] = 0x7fffffff; }   // pad to a multiple of four
   __syncthreads();
   // exact rank by (key desc, id asc): four lanes per entry, each comparing against a quarter of
-  // the list (uint4 reads), partial ranks summed by shuffle
+  // the list (uint4 reads), partial ranks summed inside the quad; the rank is the output slot
   const int part = tid & 3;
   const uint4* s_key4 = (const uint4*)s_key;
   const int4* s_idx4 = (const int4*)s_idx;
@@ -113,30 +128,11 @@ __device__ __forceinline__ bool select_pivot(const float4 (&v)[PIVOT_NV4], int K
       rank += (kv.z > me) || (kv.z == me && d.z < mid);
       rank += (kv.w > me) || (kv.w == me && d.w < mid);
     }
-    rank += __shfl_xor(rank, 1);
-    rank += __shfl_xor(rank, 2);
-    if (part == 0 && e < n) s_flag[e] = rank < K;
-  }
-  __syncthreads();
-  // ordered compaction of the flagged entries (entries tid and tid + BLOCK)
-  uint32_t flags = 0;
-#pragma unroll
-  for (int j = 0; j < PIVOT_CAP / BLOCK; ++j) {
-    const int e = tid + j * BLOCK;
-    if (e < n && s_flag[e]) flags |= 1u << (16 * j);
-  }
-  uint32_t tot2;
-  const uint32_t ex = block_excl_scan_u32<BLOCK>(flags, s_scan, &tot2);
-  const uint32_t first_half = tot2 & 0xffffu;
-#pragma unroll
-  for (int j = 0; j < PIVOT_CAP / BLOCK; ++j) {
-    if (flags & (1u << (16 * j))) {
-      const uint32_t o = j == 0 ? (ex & 0xffffu) : first_half + (ex >> 16);
-      const int id = s_idx[tid + j * BLOCK];
-      if (o < (uint32_t)K) {
-        if (use_lds) { out_lds[o] = id; out_att_lds[o] = key_to_att(s_key[tid + j * BLOCK]); }
-        out_g[o] = id;
-      }
+    rank += dpp_i<0xB1, 0xf>(0, rank);                     // quad_perm [1,0,3,2]
+    rank += dpp_i<0x4E, 0xf>(0, rank);                     // quad_perm [2,3,0,1]
+    if (part == 0 && e < n && rank < K) {
+      if (use_lds) { out_lds[rank] = mid; out_att_lds[rank] = key_to_att(me); }
+      out_g[rank] = mid;
     }
   }
   return true;
@@ -359,8 +355,8 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
           if (jb == 3 || je == 3) arow_r[k].w = ninf;
         }
       }
-      ok = select_pivot<BLOCK>(arow_r, K, p.blank_id, p.eos_id, s_work, (int32_t*)(s_work + PIVOT_CAP),
-                               (int32_t*)(s_work + 2 * PIVOT_CAP), s_scan, s_w, smallk, s_cid, s_av, g_cid);
+      ok = select_pivot<BLOCK>(arow_r, K, p.blank_id, p.eos_id, s_work, (int32_t*)(s_work + PIVOT_CAP + 4),
+                               s_w, smallk, s_cid, s_av, g_cid);
     }
     if (!ok) select_radix<BLOCK>(arow, V, K, p.blank_id, p.eos_id, s_work, s_scan, s_sel, smallk, s_cid, s_av, g_cid);
   } else {
