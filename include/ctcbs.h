@@ -87,6 +87,9 @@ typedef struct {
                            stream, at the count of finished utterances the device has
                            published (it may lag by up to two such intervals) and keeps the
                            host from running further ahead than that; 0: never             */
+  int32_t att_is_logits; /* 0: ctcbs_step takes log-probabilities p^a; 1: it takes the decoder's
+                           unnormalised output scores and applies log_softmax over the V ids of
+                           each row itself (folded into the candidate pass; Eq. (2)'s p^a)  */
   void* stream;         /* hipStream_t; NULL = the null stream                             */
 } ctcbs_config_t;
 

@@ -41,6 +41,7 @@ struct Params {
   // sizes and configuration
   int32_t U, V, Wb, K, Tp, t_max, blank_id, eos_id;
   int32_t restricted;        // 1: top-K attention candidates; 0: every id but blank/eos
+  int32_t att_logits;        // 1: the step input holds unnormalised logits (log_softmax folded in)
   int32_t win_m1, win_m2, end_flags, end_m, end_c, eos_run, l_cap;
   float end_d;
   double lambda, beta;

@@ -115,6 +115,7 @@ static int validate(const ctcbs_config_t* c) {
   if ((c->end_flags & CTCBS_END_TAU_COUNT) && c->end_c < 0) return CTCBS_EINVAL;
   if ((c->end_flags & CTCBS_END_EOS_RUN) && (c->eos_run < 1 || c->eos_run > MAX_EOS_RUN)) return CTCBS_EINVAL;
   if (c->poll_every < 0) return CTCBS_EINVAL;
+  if (c->att_is_logits != 0 && c->att_is_logits != 1) return CTCBS_EINVAL;
   if ((long long)c->n_utt * c->beam > (1ll << 24)) return CTCBS_EINVAL;
   return CTCBS_OK;
 }
@@ -166,6 +167,7 @@ static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens)
   p.end_m = (c.end_m >= 1 && c.end_m <= MAX_END_M) ? c.end_m : 1;
   p.end_c = c.end_c; p.eos_run = c.eos_run; p.end_d = c.end_d;
   p.lambda = (double)c.ctc_weight; p.beta = (double)c.length_bonus;
+  p.att_logits = c.att_is_logits ? 1 : 0;
 
   // capacity for any batch of lengths <= t_max (the step cap grows with the length)
   h->l_cap_alloc = step_cap(&c, c.t_max);

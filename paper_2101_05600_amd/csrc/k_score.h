@@ -237,6 +237,36 @@ __device__ __forceinline__ float lse_finish(Lse a) {
   return (M < LOG0_CLASS) ? LOG0F : M + __logf(s);
 }
 
+// log-sum-exp of a whole attention row (logits mode): per-lane float partials over the values
+// `get(i)` hands out, block maximum and block sum through LDS, the sum and the logarithm in fp64.
+template <int BLOCK, typename F>
+__device__ __forceinline__ float block_row_lse(int n_mine, F get, float* s_red /*[2 * BLOCK / 64]*/) {
+  constexpr int NW = BLOCK / 64;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  float m = -3.0e38f;
+  for (int i = 0; i < n_mine; ++i) m = fmaxf(m, get(i));
+  m = row16_max(m);
+  m = fmaxf(fmaxf(lane_f(m, 0), lane_f(m, 16)), fmaxf(lane_f(m, 32), lane_f(m, 48)));
+  __syncthreads();
+  if (lane == 0) s_red[w] = m;
+  __syncthreads();
+  float M = s_red[0];
+#pragma unroll
+  for (int i = 1; i < NW; ++i) M = fmaxf(M, s_red[i]);
+  float sum = 0.0f;
+  for (int i = 0; i < n_mine; ++i) sum += __expf(get(i) - M);
+  sum = row16_sum(sum);
+  const double ws = ((double)lane_f(sum, 0) + (double)lane_f(sum, 16)) + ((double)lane_f(sum, 32) + (double)lane_f(sum, 48));
+  double* s_d = (double*)(s_red + NW + (NW & 1));
+  __syncthreads();
+  if (lane == 0) s_d[w] = ws;
+  __syncthreads();
+  double tot = 0.0;
+#pragma unroll
+  for (int i = 0; i < NW; ++i) tot += s_d[i];
+  return (float)((double)M + log(tot));
+}
+
 template <int BLOCK, int LPC, int CB, int IT>
 __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const float* __restrict__ att,
                                                  int l, int cur) {
@@ -246,6 +276,7 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
   __shared__ uint32_t s_sel[2];
   __shared__ float s_e2w[(BLOCK / 64) * MAX_EOS_RUN + 1];
   __shared__ int s_nvalid;
+  __shared__ __align__(8) float s_red[4 * (BLOCK / 64) + 2];
 
   const int tid = threadIdx.x;
   const int grp = blockIdx.x;
@@ -301,6 +332,27 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
     for (int k = 0; k < PIVOT_NV4; ++k) arow_r[k] = a4[min(tid + k * BLOCK, nv4 - 1)];
   }
 
+  // logits mode: the row holds unnormalised scores; log_softmax is folded in here (the order of
+  // the ids is the same, only the values the scores use are shifted by the row's log-sum-exp)
+  float row_lse = 0.0f;
+  if (p.att_logits) {
+    if (in_regs) {
+      const int nv4 = V >> 2;
+      int cnt4 = 0;
+#pragma unroll
+      for (int k = 0; k < PIVOT_NV4; ++k) cnt4 += (tid + k * BLOCK) < nv4;
+      row_lse = block_row_lse<BLOCK>(4 * cnt4, [&](int i) {
+        float4 r = arow_r[0];
+#pragma unroll
+        for (int k = 1; k < PIVOT_NV4; ++k) if ((i >> 2) == k) r = arow_r[k];
+        return (i & 3) == 0 ? r.x : ((i & 3) == 1 ? r.y : ((i & 3) == 2 ? r.z : r.w));
+      }, s_red);
+    } else {
+      const int n_mine = tid < V ? (V - tid + BLOCK - 1) / BLOCK : 0;
+      row_lse = block_row_lse<BLOCK>(n_mine, [&](int i) { return arow[tid + i * BLOCK]; }, s_red);
+    }
+  }
+
   // ---------------- window (needs only g's record) ----------------------------------------
   int s = l > 1 ? l : 1, e = T;
   if (p.win_m1 >= 0) s = max(s, tau - p.win_m1);
@@ -316,7 +368,7 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
   float eos_n = LOG0F, eos_b = LOG0F, eos_a = 0.0f;
   if (tid == 0) {
     if (rs <= T && re >= T) { eos_n = gn[T]; eos_b = gb[T]; }
-    eos_a = arow[p.eos_id];
+    eos_a = arow[p.eos_id];               // (logits mode: shifted by the row's log-sum-exp below)
   }
 
   TRACE_POINT(p, grp, 1);
@@ -407,12 +459,12 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
       for (int i = q + IT * LPC; i < n4; i += LPC) lse_add4(a, col[i], f4[i]);
       const float inc = (W > 0) ? lse_finish<LPC>(a) : LOG0F;
       if (q == 0) {
-        const float av = smallk ? s_av[c] : arow[id];
+        const float av = (smallk ? s_av[c] : arow[id]) - row_lse;
         const bool valid = inc > LOG0_CLASS;
         const double ctc = valid ? off + (double)inc : LOG0D;
         const double J = valid ? lam * ctc + (1.0 - lam) * (double)av + jbase : LOG0D;
         g_inc[c] = inc; g_catt[c] = av; g_ctc[c] = ctc; g_joint[c] = J;
-        if (smallk) { s_J[c] = (valid && J == J) ? J : LOG0D; s_inc[c] = inc; }
+        if (smallk) { s_J[c] = (valid && J == J) ? J : LOG0D; s_inc[c] = inc; s_av[c] = av; }
       }
     }
   }
@@ -424,7 +476,7 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
     const bool v = ce > LOG0_CLASS;
     const double ctc = v ? off + (double)ce : LOG0D;
     p.ctc_eos[grp] = ctc;
-    p.joint_eos[grp] = v ? lam * ctc + (1.0 - lam) * (double)eos_a + jbase : LOG0D;
+    p.joint_eos[grp] = v ? lam * ctc + (1.0 - lam) * (double)(eos_a - row_lse) + jbase : LOG0D;
     p.win_s[grp] = s; p.win_e[grp] = e;
     p.grp_cells[grp] = (long long)K * (long long)W;
   }

@@ -87,7 +87,7 @@ class GpuDecoder:
 
 
 def lockstep_decode(w, ctc, lens, peek=True, check_utts=None, max_steps=None, progress=None,
-                    att_fn=None):
+                    att_fn=None, gpu_att_fn=None):
     """Decode the batch on the GPU with host-generated attention rows, validating every step of
     the utterances in check_utts (default: all) against the oracle.  Returns (report, results)."""
     U, Wb = len(lens), w["beam"]
@@ -104,10 +104,9 @@ def lockstep_decode(w, ctc, lens, peek=True, check_utts=None, max_steps=None, pr
             step += 1
             if max_steps is not None and step > max_steps:
                 break
-            att = host_att(w, step, hashes, live, U)
-            if att_fn is not None:
-                att = att_fn(att)
-            rc = dec.step(att)
+            raw = host_att(w, step, hashes, live, U)
+            att = att_fn(raw) if att_fn is not None else raw
+            rc = dec.step(gpu_att_fn(raw) if gpu_att_fn is not None else att)
             if rc == dec.m.DONE:
                 break
             out = dec.outputs()

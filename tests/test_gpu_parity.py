@@ -332,3 +332,43 @@ def test_abi_rejects_bad_arguments():
     assert m.ctcbs_strerror(m.ECAP) and m.ctcbs_strerror(-77)
     L.ctcbs_destroy(h)
     L.ctcbs_destroy(None)
+
+
+def test_full_vocabulary_large_v_matches_oracle():
+    """The unrestricted stress shape in miniature: every one of V-2 = 4998 ids scored per hypothesis
+    (whole-wave chains over the full frame range, group lists by repeated arg-max)."""
+    w = small("cfg4a", n_utt=2, t_lo=70, t_hi=131, beam=3, max_len_ratio=0.0, max_len_abs=9)
+    lens, ctc = make_inputs(w)
+    rep, res = lockstep_decode(w, ctc, lens, peek=True)
+    print(rep)
+    assert rep["max_score_err"] < 1e-4 and rep["max_ctc_err"] < 1e-4
+    assert res["cells"] == int(res["oracle_cells"])
+
+
+@pytest.mark.parametrize("shape", ["regs", "odd_vocab", "full_v"])
+def test_logits_mode_folds_log_softmax_in(shape):
+    """att_is_logits = 1: the library normalises the decoder's raw scores itself; the oracle is fed the
+    fp64 log_softmax of the very same fp32 logits."""
+    over = dict(n_utt=3, t_lo=40, t_hi=100, vocab=1000, beam=4, cand_k=20, win_m1=20, win_m2=20,
+                end_flags=7, eos_run=5)
+    if shape == "odd_vocab":
+        over.update(vocab=997)                       # not a multiple of four: the slower selection path
+    elif shape == "full_v":
+        over.update(vocab=120, cand_k=0)
+    w = small("cfg1", **over)
+    lens, ctc = make_inputs(w)
+
+    def logits(a):                                   # per-row shift and scale-free noise: a valid logit row
+        shift = np.nan_to_num(a[..., 5:6]) * 0.37 + 2.5
+        return (a.astype(np.float64) + shift).astype(np.float32)
+
+    def normalised(a):
+        z = logits(a).astype(np.float64)
+        m = np.nanmax(z, axis=-1, keepdims=True)
+        lse = m + np.log(np.nansum(np.exp(z - m), axis=-1, keepdims=True))
+        return (z - lse).astype(np.float32)
+
+    wg = dict(w); wg["att_is_logits"] = 1
+    rep, res = lockstep_decode(wg, ctc, lens, att_fn=normalised, gpu_att_fn=logits)
+    print(shape, rep)
+    assert rep["max_score_err"] < 1e-4 and rep["max_ctc_err"] < 1e-4 and rep["utt_steps"] > 20
