@@ -200,6 +200,7 @@ def cpu_baseline(batch, n_sample):
         "vocab", "beam", "blank_id", "eos_id", "cand_k", "win_m1", "win_m2", "ctc_weight",
         "length_bonus", "max_len_ratio", "max_len_abs", "end_flags", "end_m", "end_d", "end_c",
         "eos_run")}
+    kw["win_union"] = w.get("win_union", 0)
     for k in ("ctc_weight", "length_bonus", "max_len_ratio", "end_d"):
         kw[k] = float(np.float32(kw[k]))          # the values the fp32 fields of the C ABI carry
     cfg = oracle.make_cfg(**kw)

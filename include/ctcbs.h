@@ -87,6 +87,9 @@ typedef struct {
                            stream, at the count of finished utterances the device has
                            published (it may lag by up to two such intervals) and keeps the
                            host from running further ahead than that; 0: never             */
+  int32_t win_union;    /* 0: every hypothesis has its own window (the two equations for s_ij, e_ij);
+                           1: one window for the whole batch, s^l = min_ij s_ij, e^l = max_ij
+                           e_ij (last two equations of Sec. 3.2.3), cut at each T_i          */
   int32_t att_is_logits; /* 0: ctcbs_step takes log-probabilities p^a; 1: it takes the decoder's
                            unnormalised output scores and applies log_softmax over the V ids of
                            each row itself (folded into the candidate pass; Eq. (2)'s p^a)  */

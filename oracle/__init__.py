@@ -28,7 +28,8 @@ class OrcCfg(ctypes.Structure):
                 ("eos_id", ctypes.c_int32), ("cand_k", ctypes.c_int32), ("win_m1", ctypes.c_int32),
                 ("win_m2", ctypes.c_int32), ("max_len_abs", ctypes.c_int32),
                 ("end_flags", ctypes.c_int32), ("end_m", ctypes.c_int32), ("end_c", ctypes.c_int32),
-                ("eos_run", ctypes.c_int32), ("ctc_weight", ctypes.c_double),
+                ("eos_run", ctypes.c_int32), ("win_union", ctypes.c_int32), ("pad_", ctypes.c_int32),
+                ("ctc_weight", ctypes.c_double),
                 ("length_bonus", ctypes.c_double), ("max_len_ratio", ctypes.c_double),
                 ("end_d", ctypes.c_double)]
 
@@ -87,6 +88,9 @@ def lib():
         L.orc_prefix_and_full.argtypes = [vp, i32, i32, i32, vp, i32, ctypes.POINTER(dbl),
                                           ctypes.POINTER(dbl)]
         L.orc_batch_step_auto.argtypes = [vp, i32, vp, vp]
+        L.orc_union_contrib.restype = i32
+        L.orc_union_contrib.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+        L.orc_set_union.argtypes = [vp, i32, i32]
         L.orc_end_detect.restype = i32
         L.orc_end_detect.argtypes = [ctypes.POINTER(OrcCfg), i32, i32, i32, vp, vp, vp,
                                      ctypes.POINTER(dbl)]
@@ -107,7 +111,7 @@ def _view(ptr, dtype, n):
 
 def make_cfg(vocab, beam, blank_id=0, eos_id=None, cand_k=0, win_m1=-1, win_m2=-1, ctc_weight=0.3,
              length_bonus=0.0, max_len_ratio=0.0, max_len_abs=0, end_flags=3, end_m=3, end_d=-10.0,
-             end_c=2, eos_run=10, **_ignored):
+             end_c=2, eos_run=10, win_union=0, **_ignored):
     c = OrcCfg()
     c.vocab, c.beam, c.blank_id = vocab, beam, blank_id
     c.eos_id = vocab - 1 if eos_id is None else eos_id
@@ -115,6 +119,7 @@ def make_cfg(vocab, beam, blank_id=0, eos_id=None, cand_k=0, win_m1=-1, win_m2=-
     c.ctc_weight, c.length_bonus = ctc_weight, length_bonus
     c.max_len_ratio, c.max_len_abs = max_len_ratio, max_len_abs
     c.end_flags, c.end_m, c.end_d, c.end_c, c.eos_run = end_flags, end_m, end_d, end_c, eos_run
+    c.win_union = win_union
     return c
 
 
@@ -193,6 +198,15 @@ class OracleUtt:
         te = None if tau_end is None else np.ascontiguousarray(tau_end, dtype=np.int32)
         self.L.orc_override(self.h, None if t is None else _p(t), None if te is None else _p(te),
                             int(finished))
+
+    def union_contrib(self):
+        a, b = ctypes.c_int32(), ctypes.c_int32()
+        if not self.L.orc_union_contrib(self.h, ctypes.byref(a), ctypes.byref(b)):
+            return None
+        return a.value, b.value
+
+    def set_union(self, tau_min, e_max):
+        self.L.orc_set_union(self.h, int(tau_min), int(e_max))
 
     def step_auto(self, att):
         att = np.ascontiguousarray(att, dtype=np.float32)

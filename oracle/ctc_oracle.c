@@ -51,6 +51,8 @@ typedef struct {
   int32_t win_m1, win_m2;  /* M1, M2 of the window equations; < 0: unrestricted           */
   int32_t max_len_abs;     /* 0: none                                                       */
   int32_t end_flags, end_m, end_c, eos_run;
+  int32_t win_union;       /* 1: one window for the whole batch (last two equations of Sec. 3.2.3) */
+  int32_t pad_;
   double ctc_weight, length_bonus, max_len_ratio, end_d;
 } orc_cfg;
 
@@ -95,6 +97,7 @@ typedef struct orc_utt {
   double *child_max_n, *child_max_b;              /* [beam] max of gn / gb over the tau range */
   int32_t *child_lo;                              /* [beam] lower end of the tau range      */
   double e1_margin;        /* distance of the deciding comparison from its threshold        */
+  int32_t union_tau_min, union_e_max;   /* batch-wide values, set by the caller before each score   */
 } orc_utt;
 
 static double lae(double a, double b) {
@@ -241,8 +244,14 @@ int orc_score(orc_utt* u, const float* att) {
     select_candidates(u, a, K, ids);
     /* window: Sec. 3.2.3, the equations for s and e; unrestricted = Eq. (3) limits */
     int s, e;
-    if (c->win_m1 >= 0) { s = g->tau - c->win_m1; if (s < l) s = l; if (s < 1) s = 1; } else s = l;
-    if (c->win_m2 >= 0) { e = g->tau_end + c->win_m2; if (e > T) e = T; } else e = T;
+    if (c->win_union) {
+      /* s^l = min_ij s_ij, e^l = max_ij e_ij over the whole batch; an utterance has no frames beyond T */
+      if (c->win_m1 >= 0) { s = u->union_tau_min - c->win_m1; if (s < l) s = l; if (s < 1) s = 1; } else s = l;
+      if (c->win_m2 >= 0) { e = u->union_e_max; if (e > T) e = T; } else e = T;
+    } else {
+      if (c->win_m1 >= 0) { s = g->tau - c->win_m1; if (s < l) s = l; if (s < 1) s = 1; } else s = l;
+      if (c->win_m2 >= 0) { e = g->tau_end + c->win_m2; if (e > T) e = T; } else e = T;
+    }
     u->win_s[j] = s; u->win_e[j] = e;
     if (e >= s) u->cells += (double)K * (double)(e - s + 1);
     for (int i = 0; i < K; ++i) {
@@ -431,6 +440,23 @@ int orc_commit(orc_utt* u, int n_sel, const int32_t* sel_parent, const int32_t* 
   u->finished = fin;
   return fin;
 }
+
+/* Batch-union window: this utterance's share (min tau, max of min(tau~ + M2, T)) over its live
+ * hypotheses; returns 0 if it has none (finished or empty beam). */
+int orc_union_contrib(const orc_utt* u, int32_t* tau_min, int32_t* e_max) {
+  int any = 0;
+  if (u->finished) return 0;
+  for (int j = 0; j < u->cfg.beam; ++j) {
+    const orc_hyp* g = &u->cur[j];
+    if (!g->live) continue;
+    int e = g->tau_end + u->cfg.win_m2; if (e > u->T) e = u->T;
+    if (!any || g->tau < *tau_min) *tau_min = g->tau;
+    if (!any || e > *e_max) *e_max = e;
+    any = 1;
+  }
+  return any;
+}
+void orc_set_union(orc_utt* u, int32_t tau_min, int32_t e_max) { u->union_tau_min = tau_min; u->union_e_max = e_max; }
 
 /* Adopt externally validated values for the new beam's time indices / the finished flag. */
 void orc_override(orc_utt* u, const int32_t* tau, const int32_t* tau_end, int finished) {

@@ -55,6 +55,13 @@ class Lockstep:
         peek: optional dict cand_id, cand_ctc, cand_joint, win_s, win_e, ctc_eos, joint_eos."""
         eps, B, rep = self.eps, self.B, self.report
         rep["steps"] += 1
+        if self.cfg.win_union:
+            # one window for the whole batch: needs every utterance of the batch in this check
+            shares = [c for c in (o.union_contrib() for o in self.utts) if c is not None]
+            if shares:
+                tmin, emax = min(c[0] for c in shares), max(c[1] for c in shares)
+                for o in self.utts:
+                    o.set_union(tmin, emax)
         for o, u in zip(self.utts, self.ids):
             if o.finished:
                 if not out["finished"][u]:

@@ -43,7 +43,8 @@ class Config(ctypes.Structure):
                 ("max_len_ratio", ctypes.c_float), ("max_len_abs", ctypes.c_int32),
                 ("end_flags", ctypes.c_int32), ("end_m", ctypes.c_int32), ("end_d", ctypes.c_float),
                 ("end_c", ctypes.c_int32), ("eos_run", ctypes.c_int32), ("poll_every", ctypes.c_int32),
-                ("att_is_logits", ctypes.c_int32), ("stream", ctypes.c_void_p)]
+                ("win_union", ctypes.c_int32), ("att_is_logits", ctypes.c_int32),
+                ("stream", ctypes.c_void_p)]
 
 
 class StepOut(ctypes.Structure):
@@ -113,7 +114,7 @@ def _ptr(t):
 def make_config(n_utt, t_max, vocab, beam, blank_id=0, eos_id=None, cand_k=0, win_m1=-1, win_m2=-1,
                 ctc_weight=0.3, length_bonus=0.0, max_len_ratio=0.0, max_len_abs=0, end_flags=3,
                 end_m=3, end_d=-10.0, end_c=2, eos_run=10, poll_every=0, stream=None, att_is_logits=0,
-                **_ignored):
+                win_union=0, **_ignored):
     c = Config()
     c.n_utt, c.t_max, c.vocab, c.beam, c.blank_id = n_utt, t_max, vocab, beam, blank_id
     c.eos_id = vocab - 1 if eos_id is None else eos_id
@@ -123,6 +124,7 @@ def make_config(n_utt, t_max, vocab, beam, blank_id=0, eos_id=None, cand_k=0, wi
     c.end_flags, c.end_m, c.end_d, c.end_c, c.eos_run = end_flags, end_m, end_d, end_c, eos_run
     c.poll_every = poll_every
     c.att_is_logits = att_is_logits
+    c.win_union = win_union
     c.stream = stream
     return c
 

@@ -42,6 +42,7 @@ struct Params {
   int32_t U, V, Wb, K, Tp, t_max, blank_id, eos_id;
   int32_t restricted;        // 1: top-K attention candidates; 0: every id but blank/eos
   int32_t att_logits;        // 1: the step input holds unnormalised logits (log_softmax folded in)
+  int32_t win_union;         // 1: one window for the whole batch (min start / max end over all hypotheses)
   int32_t win_m1, win_m2, end_flags, end_m, end_c, eos_run, l_cap;
   float end_d;
   double lambda, beta;
@@ -89,6 +90,7 @@ struct Params {
   unsigned long long* cells; // [U] prefix-score terms so far
   unsigned long long* groups;// [U] live (utterance, beam) groups so far
   int32_t* n_finished;       // [1]
+  int32_t* union_win;        // [2][2] per step parity: (min tau, max of min(tau~ + M2, T)) over live hypotheses
   int32_t* host_finished;    // [1] host-resident copy (device-mapped pinned memory), one step behind
   // back-pointer trie, level l holds the hypotheses of length l: [l_cap+1][U][Wb]
   int32_t* trie_parent;

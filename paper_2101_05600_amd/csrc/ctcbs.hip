@@ -35,6 +35,7 @@ struct ctcbs {
   int32_t l_cap;       // largest step cap over the batch
   int32_t l_cap_alloc; // step cap of an utterance of t_max frames: what the buffers are sized for
   int32_t *d_lens, *d_lmax;
+  int32_t union_init[4];
   int32_t known_finished;
   size_t score_smem_bytes;
   int score_block, score_lpc, select_block;
@@ -116,6 +117,7 @@ static int validate(const ctcbs_config_t* c) {
   if ((c->end_flags & CTCBS_END_EOS_RUN) && (c->eos_run < 1 || c->eos_run > MAX_EOS_RUN)) return CTCBS_EINVAL;
   if (c->poll_every < 0) return CTCBS_EINVAL;
   if (c->att_is_logits != 0 && c->att_is_logits != 1) return CTCBS_EINVAL;
+  if (c->win_union != 0 && c->win_union != 1) return CTCBS_EINVAL;
   if ((long long)c->n_utt * c->beam > (1ll << 24)) return CTCBS_EINVAL;
   return CTCBS_OK;
 }
@@ -138,6 +140,13 @@ static int ingest(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens) {
   const size_t UW = (size_t)U * p.Wb;
   HIPCHK(hipMemcpyAsync(h->d_lens, h->lens.data(), sizeof(int32_t) * U, hipMemcpyHostToDevice, st));
   HIPCHK(hipMemcpyAsync(h->d_lmax, h->lmax.data(), sizeof(int32_t) * U, hipMemcpyHostToDevice, st));
+  {
+    // step 1: every hypothesis is empty, tau = tau~ = 0
+    int e_max = 0;
+    for (int u = 0; u < U; ++u) { int e = c.win_m2 < h->lens[u] ? c.win_m2 : h->lens[u]; if (e > e_max) e_max = e; }
+    h->union_init[0] = 0x7fffffff; h->union_init[1] = -1; h->union_init[2] = 0; h->union_init[3] = e_max;
+    HIPCHK(hipMemcpyAsync(p.union_win, h->union_init, sizeof(h->union_init), hipMemcpyHostToDevice, st));
+  }
   HIPCHK(hipMemsetAsync(p.grp_n, 0, sizeof(int32_t) * UW, st));
   HIPCHK(hipMemsetAsync(p.stopped, 0, sizeof(int32_t) * UW, st));
   dim3 tg((p.V + 63) / 64, (c.t_max + 4 + 63) / 64, U);
@@ -168,6 +177,7 @@ static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens)
   p.end_c = c.end_c; p.eos_run = c.eos_run; p.end_d = c.end_d;
   p.lambda = (double)c.ctc_weight; p.beta = (double)c.length_bonus;
   p.att_logits = c.att_is_logits ? 1 : 0;
+  p.win_union = c.win_union ? 1 : 0;
 
   // capacity for any batch of lengths <= t_max (the step cap grows with the length)
   h->l_cap_alloc = step_cap(&c, c.t_max);
@@ -194,7 +204,7 @@ static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens)
   A(p.grp_inc, UW * Wb); A(p.grp_att, UW * Wb);
   A(p.ctc_eos, UW); A(p.joint_eos, UW); A(p.stopped, UW); A(p.grp_cells, UW);
   A(p.utt, (size_t)U); A(p.finished, (size_t)U); A(p.cells, (size_t)U); A(p.groups, (size_t)U);
-  A(p.n_finished, (size_t)1);
+  A(p.n_finished, (size_t)1); A(p.union_win, (size_t)4);
   const size_t trie_n = (size_t)(h->l_cap_alloc + 1) * UW;
   A(p.trie_parent, trie_n); A(p.trie_token, trie_n); A(p.trie_tau, trie_n);
   A(p.out_parent, UW); A(p.out_token, UW); A(p.out_score, UW); A(p.out_live, UW);

@@ -289,6 +289,9 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
   if (grp == 0 && tid == 0) {
     *(volatile int32_t*)p.host_finished = *p.n_finished;
     __threadfence_system();
+    // batch-union window: clear the slot the select kernel of this step will fill for the next one
+    p.union_win[2 * ((l + 1) & 1)] = 0x7fffffff;
+    p.union_win[2 * ((l + 1) & 1) + 1] = -1;
   }
 
   // ---------------- first round of loads: g's record and its attention row ----------------
@@ -355,8 +358,13 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
 
   // ---------------- window (needs only g's record) ----------------------------------------
   int s = l > 1 ? l : 1, e = T;
-  if (p.win_m1 >= 0) s = max(s, tau - p.win_m1);
-  if (p.win_m2 >= 0) e = min(e, tau_end + p.win_m2);
+  if (p.win_union) {            // s^l = min_ij s_ij, e^l = max_ij e_ij (last two equations of Sec. 3.2.3)
+    if (p.win_m1 >= 0) s = max(s, p.union_win[2 * (l & 1)] - p.win_m1);
+    if (p.win_m2 >= 0) e = min(e, p.union_win[2 * (l & 1) + 1]);
+  } else {
+    if (p.win_m1 >= 0) s = max(s, tau - p.win_m1);
+    if (p.win_m2 >= 0) e = min(e, tau_end + p.win_m2);
+  }
   const int W = e >= s ? e - s + 1 : 0;
   const int t0 = s & ~3;                                   // column loads start on a 16-byte boundary
   const int n4 = W > 0 ? ((e - t0) >> 2) + 1 : 0;

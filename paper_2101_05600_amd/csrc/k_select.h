@@ -74,6 +74,7 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
   __shared__ long long o_cells[MAX_BEAM];
   __shared__ double o_je[MAX_BEAM], o_hatt[MAX_BEAM], o_off[MAX_BEAM];
   __shared__ int s_fin;
+  __shared__ int s_ntau[MAX_BEAM], s_ntau_end[MAX_BEAM];   // time indices of the new hypotheses
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int u = blockIdx.x, Wb = p.Wb;
@@ -298,6 +299,7 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
       p.h_tau[nxt][h0 + n] = arg_n; p.h_tau_end[nxt][h0 + n] = arg_b;
       p.out_tau[h0 + n] = arg_n; p.out_tau_end[h0 + n] = arg_b;
       p.trie_tau[trie_l + n] = arg_n;
+      s_ntau[n] = arg_n; s_ntau_end[n] = arg_b;
     }
   }
   __syncthreads();
@@ -316,6 +318,10 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
       p.h_off[nxt][h] = o_off[par] + (double)s_inc[e];
       p.h_att[nxt][h] = o_hatt[par] + (double)s_att[e];
       p.h_joint[nxt][h] = s_J[e];
+      if (p.win_union && !fin) {                 // this hypothesis's share of the next step's window
+        atomicMin(&p.union_win[2 * ((l + 1) & 1)], s_ntau[n]);
+        atomicMax(&p.union_win[2 * ((l + 1) & 1) + 1], min(s_ntau_end[n] + p.win_m2, T));
+      }
     } else {
       p.out_parent[h] = -1; p.out_token[h] = -1; p.out_score[h] = LOG0F; p.out_live[h] = 0;
       p.out_tau[h] = 0; p.out_tau_end[h] = 0;

@@ -15,6 +15,7 @@ def orc_cfg_from(w):
         "vocab", "beam", "blank_id", "eos_id", "cand_k", "win_m1", "win_m2", "ctc_weight",
         "length_bonus", "max_len_ratio", "max_len_abs", "end_flags", "end_m", "end_d", "end_c",
         "eos_run")}
+    kw["win_union"] = w.get("win_union", 0)
     # the C ABI carries these three as fp32: give the oracle the same values
     for k in ("ctc_weight", "length_bonus", "max_len_ratio", "end_d"):
         kw[k] = float(np.float32(kw[k]))

@@ -372,3 +372,20 @@ def test_logits_mode_folds_log_softmax_in(shape):
     rep, res = lockstep_decode(wg, ctc, lens, att_fn=normalised, gpu_att_fn=logits)
     print(shape, rep)
     assert rep["max_score_err"] < 1e-4 and rep["max_ctc_err"] < 1e-4 and rep["utt_steps"] > 20
+
+
+@pytest.mark.parametrize("m1,m2", [(5, 20), (5, -1), (12, 12)])
+def test_batch_union_window(m1, m2):
+    """The paper's batch-wide window (s^l = min s_ij, e^l = max e_ij) with its own margins M1 = 5, M2 in
+    {20, inf}: every utterance of the batch is followed, the union couples them."""
+    w = small("cfg1", n_utt=4, t_lo=45, t_hi=150, vocab=600, beam=4, cand_k=16, win_m1=m1, win_m2=m2,
+              end_flags=3, win_union=1)
+    lens, ctc = make_inputs(w)
+    rep, res = lockstep_decode(w, ctc, lens)
+    print(rep, res["cells"])
+    assert rep["max_score_err"] < 1e-4 and rep["max_ctc_err"] < 1e-4
+    assert res["cells"] == int(res["oracle_cells"])
+    # the union window is never narrower than the per-hypothesis one: at least as many terms
+    w2 = dict(w); w2["win_union"] = 0
+    rep2, res2 = lockstep_decode(w2, ctc, lens)
+    assert res["cells"] / res["steps"] >= res2["cells"] / res2["steps"] * 0.999

@@ -598,3 +598,32 @@ def test_lmax():
     assert L.orc_lmax(ctypes.byref(make_cfg(vocab=5, beam=1, max_len_abs=20)), 100) == 20
     assert L.orc_lmax(ctypes.byref(make_cfg(vocab=5, beam=1)), 7) == 7
     assert L.orc_lmax(ctypes.byref(make_cfg(vocab=5, beam=1, max_len_ratio=0.3)), 2) == 1
+
+
+# --------------------------------------------------------------------------------------
+# Batch-wide window (last two equations of Sec. 3.2.3)
+# --------------------------------------------------------------------------------------
+def test_union_window_is_min_start_max_end_over_the_batch():
+    xs = [small_workload(T=70, V=9, seed=31), small_workload(T=45, V=9, seed=32)]
+    base = dict(vocab=9, beam=3, cand_k=0, win_m1=4, win_m2=6, max_len_abs=12, end_flags=0)
+    us = [OracleUtt(x, make_cfg(win_union=1, **base)) for x in xs]
+    for step in range(1, 11):
+        shares = [o.union_contrib() for o in us]
+        live = [c for c in shares if c is not None]
+        tmin, emax = min(c[0] for c in live), max(c[1] for c in live)
+        # each share is (min tau, max min(tau~ + M2, T)) over that utterance's live hypotheses
+        for o, c in zip(us, shares):
+            hyps = [o.hyp(j) for j in range(3) if o.hyp(j)["live"]]
+            assert c == (min(h["tau"] for h in hyps), max(min(h["tau_end"] + 6, o.T) for h in hyps))
+        for i, o in enumerate(us):
+            o.set_union(tmin, emax)
+            hyps = [o.hyp(j) for j in range(3)]
+            att = np.stack([gen.att_row(7, i, step, gen.prefix_hash(h["labels"]), 9) for h in hyps])
+            o.score(att)
+            s, e = o.windows()
+            for j, h in enumerate(hyps):
+                if h["live"]:
+                    assert s[j] == max(tmin - 4, step, 1) and e[j] == min(emax, o.T)
+                    # never narrower than the hypothesis's own window
+                    assert s[j] <= max(h["tau"] - 4, step, 1) and e[j] >= min(h["tau_end"] + 6, o.T)
+            o.commit()
