@@ -40,6 +40,11 @@ def parse():
     ap.add_argument("--inflight", type=int, default=1,
                     help="batches decoded concurrently, each on its own handle and stream (offline decoding "
                          "always has more batches queued); the default 1 is the headline figure")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the benchmark line: decode the workload under the paper's window "
+                         "settings (Table 'batch decoding': M1 = 5, M2 in {inf, 60, 40, 20}), the per-hypothesis "
+                         "and the batch-wide window, and print a table (terms, time, agreement with the "
+                         "unrestricted decode)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (known traffic, for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -245,6 +250,45 @@ def cpu_baseline(batch, n_sample):
                               "seconds": t1}}
 
 
+def sweep(a):
+    """Window ablation on the synthetic stand-in workload (no transcripts exist, so agreement with the
+    unrestricted decode takes the place of the paper's CER column)."""
+    import torch
+    import gen
+    rows = []
+    ref = None
+    variants = [("unrestricted", -1, -1, 0), ("M1=5, M2=inf", 5, -1, 0), ("M1=5, M2=60", 5, 60, 0),
+                ("M1=5, M2=40", 5, 40, 0), ("M1=5, M2=20", 5, 20, 0), ("M1=M2=50", 50, 50, 0),
+                ("M1=5, M2=60, batch-wide window", 5, 60, 1), ("M1=M2=50, batch-wide window", 50, 50, 1)]
+    for name, m1, m2, uni in variants:
+        w = gen.workload(a.workload)
+        if a.utts > 0:
+            w["n_utt"] = a.utts
+        w.update(win_m1=m1, win_m2=m2, win_union=uni)
+        b = Batch(w, a.poll_every)
+        tok, nt, sc, _, _ = b.record()
+        b.decode()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(max(a.steps // 4, 3)):
+            b.decode()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / max(a.steps // 4, 3) * 1e3
+        if ref is None:
+            ref = (tok, nt, sc)
+        same = [int(nt[u] == ref[1][u] and np.array_equal(tok[u, :nt[u]], ref[0][u, :nt[u]])) for u in range(b.U)]
+        dsc = [abs(float(sc[u]) - float(ref[2][u])) for u in range(b.U) if same[u]]
+        rows.append((name, b.cells, b.n_steps, ms, sum(same) / b.U, max(dsc) if dsc else float("nan")))
+        b.close()
+        del b
+        torch.cuda.empty_cache()
+    print(f"| window ({a.workload}) | prefix-score terms per decode | steps | ms per decode | same transcript as "
+          f"unrestricted | max score difference (same transcript) |")
+    print("|---|---|---|---|---|---|")
+    for r in rows:
+        print(f"| {r[0]} | {r[1]:.3e} | {r[2]} | {r[3]:.2f} | {100 * r[4]:.1f} % | {r[5]:.2e} |")
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -258,6 +302,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     m.lib()
+    if a.sweep:
+        sweep(a)
+        return
     w = gen.workload(a.workload)
     if a.utts > 0:
         w["n_utt"] = a.utts

@@ -237,34 +237,34 @@ __device__ __forceinline__ float lse_finish(Lse a) {
   return (M < LOG0_CLASS) ? LOG0F : M + __logf(s);
 }
 
-// log-sum-exp of a whole attention row (logits mode): per-lane float partials over the values
-// `get(i)` hands out, block maximum and block sum through LDS, the sum and the logarithm in fp64.
-template <int BLOCK, typename F>
-__device__ __forceinline__ float block_row_lse(int n_mine, F get, float* s_red /*[2 * BLOCK / 64]*/) {
+// Block-wide maximum / sum (logits mode: log-sum-exp of a whole attention row).  The per-lane
+// partials are floats; partial sums are added in fp64.
+template <int BLOCK>
+__device__ __forceinline__ float block_max_f(float m, float* s_red /*[BLOCK / 64]*/) {
   constexpr int NW = BLOCK / 64;
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  float m = -3.0e38f;
-  for (int i = 0; i < n_mine; ++i) m = fmaxf(m, get(i));
   m = row16_max(m);
   m = fmaxf(fmaxf(lane_f(m, 0), lane_f(m, 16)), fmaxf(lane_f(m, 32), lane_f(m, 48)));
   __syncthreads();
-  if (lane == 0) s_red[w] = m;
+  if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = m;
   __syncthreads();
   float M = s_red[0];
 #pragma unroll
   for (int i = 1; i < NW; ++i) M = fmaxf(M, s_red[i]);
-  float sum = 0.0f;
-  for (int i = 0; i < n_mine; ++i) sum += __expf(get(i) - M);
+  return M;
+}
+template <int BLOCK>
+__device__ __forceinline__ double block_sum_d(float sum, double* s_d /*[BLOCK / 64]*/) {
+  constexpr int NW = BLOCK / 64;
   sum = row16_sum(sum);
-  const double ws = ((double)lane_f(sum, 0) + (double)lane_f(sum, 16)) + ((double)lane_f(sum, 32) + (double)lane_f(sum, 48));
-  double* s_d = (double*)(s_red + NW + (NW & 1));
+  const double ws = ((double)lane_f(sum, 0) + (double)lane_f(sum, 16)) +
+                    ((double)lane_f(sum, 32) + (double)lane_f(sum, 48));
   __syncthreads();
-  if (lane == 0) s_d[w] = ws;
+  if ((threadIdx.x & 63) == 0) s_d[threadIdx.x >> 6] = ws;
   __syncthreads();
   double tot = 0.0;
 #pragma unroll
   for (int i = 0; i < NW; ++i) tot += s_d[i];
-  return (float)((double)M + log(tot));
+  return tot;
 }
 
 template <int BLOCK, int LPC, int CB, int IT>
@@ -276,7 +276,7 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
   __shared__ uint32_t s_sel[2];
   __shared__ float s_e2w[(BLOCK / 64) * MAX_EOS_RUN + 1];
   __shared__ int s_nvalid;
-  __shared__ __align__(8) float s_red[4 * (BLOCK / 64) + 2];
+  __shared__ __align__(8) float s_red[4 * (BLOCK / 64)];   // BLOCK/64 floats, then BLOCK/64 doubles
 
   const int tid = threadIdx.x;
   const int grp = blockIdx.x;
@@ -339,20 +339,26 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
   // the ids is the same, only the values the scores use are shifted by the row's log-sum-exp)
   float row_lse = 0.0f;
   if (p.att_logits) {
+    float* s_redf = s_red;
+    double* s_redd = (double*)(s_red + 2 * (BLOCK / 64));
+    float m = -3.0e38f, sum = 0.0f;
     if (in_regs) {
       const int nv4 = V >> 2;
-      int cnt4 = 0;
 #pragma unroll
-      for (int k = 0; k < PIVOT_NV4; ++k) cnt4 += (tid + k * BLOCK) < nv4;
-      row_lse = block_row_lse<BLOCK>(4 * cnt4, [&](int i) {
-        float4 r = arow_r[0];
+      for (int k = 0; k < PIVOT_NV4; ++k)
+        if (tid + k * BLOCK < nv4)
+          m = fmaxf(m, fmaxf(fmaxf(arow_r[k].x, arow_r[k].y), fmaxf(arow_r[k].z, arow_r[k].w)));
+      const float M = block_max_f<BLOCK>(m, s_redf);
 #pragma unroll
-        for (int k = 1; k < PIVOT_NV4; ++k) if ((i >> 2) == k) r = arow_r[k];
-        return (i & 3) == 0 ? r.x : ((i & 3) == 1 ? r.y : ((i & 3) == 2 ? r.z : r.w));
-      }, s_red);
+      for (int k = 0; k < PIVOT_NV4; ++k)
+        if (tid + k * BLOCK < nv4)
+          sum += (__expf(arow_r[k].x - M) + __expf(arow_r[k].y - M)) + (__expf(arow_r[k].z - M) + __expf(arow_r[k].w - M));
+      row_lse = (float)((double)M + log(block_sum_d<BLOCK>(sum, s_redd)));
     } else {
-      const int n_mine = tid < V ? (V - tid + BLOCK - 1) / BLOCK : 0;
-      row_lse = block_row_lse<BLOCK>(n_mine, [&](int i) { return arow[tid + i * BLOCK]; }, s_red);
+      for (int i = tid; i < V; i += BLOCK) m = fmaxf(m, arow[i]);
+      const float M = block_max_f<BLOCK>(m, s_redf);
+      for (int i = tid; i < V; i += BLOCK) sum += __expf(arow[i] - M);
+      row_lse = (float)((double)M + log(block_sum_d<BLOCK>(sum, s_redd)));
     }
   }
 
