@@ -23,8 +23,10 @@
 // shipped library).
 #ifdef CTCBS_TRACE
 #define TRACE_POINT(p, blk, i) do { if ((p).trace && threadIdx.x == 0) (p).trace[(size_t)(blk) * 16 + (i)] = wall_clock64(); } while (0)
+#define TRACE_POINT_T(p, blk, i, thr) do { if ((p).trace && threadIdx.x == (thr)) (p).trace[(size_t)(blk) * 16 + (i)] = wall_clock64(); } while (0)
 #else
 #define TRACE_POINT(p, blk, i) do { } while (0)
+#define TRACE_POINT_T(p, blk, i, thr) do { } while (0)
 #endif
 
 struct UttState {            // per utterance, touched by one thread of the select kernel
@@ -113,6 +115,15 @@ __device__ __forceinline__ float lae(float a, float b) {
   float m = fmaxf(a, b);
   float d = -fabsf(a - b);
   return m + __logf(1.0f + __expf(d));
+}
+
+// Work-group barrier for data exchanged through LDS only.  __syncthreads() also waits for the
+// wave's outstanding global loads and stores (they share one counter with nothing to tell them
+// apart); here they stay in flight: prefetched rows and columns keep arriving, and stores of
+// results nobody in this work-group reads back are not waited for.  Never use it to publish
+// global memory to other waves of the block.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
 __device__ __forceinline__ float canon0(float v) { return v < LOG0_CLASS ? LOG0F : v; }

@@ -300,7 +300,10 @@ extern "C" int ctcbs_step(ctcbs_t* h, const float* d_att_logp, ctcbs_step_out_t*
     HIPCHK(hipGetLastError());
   }
   if (ev) HIPCHK(hipEventRecord(ev[1], h->stream));
-  switch (h->select_block) {
+  if (!h->p.win_union) {
+    // per-hypothesis windows: nothing is shared across utterances, one work-group per new beam slot
+    hipLaunchKernelGGL((k_select_split<256>), dim3(h->p.U * h->p.Wb), dim3(256), 0, h->stream, h->p, l, h->cur);
+  } else switch (h->select_block) {
     case 256: hipLaunchKernelGGL((k_select<256>), dim3(h->p.U), dim3(256), 0, h->stream, h->p, l, h->cur); break;
     case 512: hipLaunchKernelGGL((k_select<512>), dim3(h->p.U), dim3(512), 0, h->stream, h->p, l, h->cur); break;
     default: hipLaunchKernelGGL((k_select<1024>), dim3(h->p.U), dim3(1024), 0, h->stream, h->p, l, h->cur); break;

@@ -64,7 +64,7 @@ __device__ __forceinline__ bool select_pivot(const float4 (&v)[PIVOT_NV4], int K
     if (__popcll(__ballot(lmax >= trial)) >= r) thr = trial;
   }
   if (lane == 0) s_w[w] = thr;
-  __syncthreads();
+  lds_barrier();
   uint32_t Lk = s_w[0];
 #pragma unroll
   for (int i = 1; i < NW; ++i) Lk = min(Lk, s_w[i]);
@@ -77,9 +77,9 @@ __device__ __forceinline__ bool select_pivot(const float4 (&v)[PIVOT_NV4], int K
   for (int k = 0; k < PIVOT_NV4; ++k)
     wave_total += __popcll(__ballot(v[k].x >= L)) + __popcll(__ballot(v[k].y >= L)) +
                   __popcll(__ballot(v[k].z >= L)) + __popcll(__ballot(v[k].w >= L));
-  __syncthreads();                                         // s_w was read by everyone
+  lds_barrier();                                         // s_w was read by everyone
   if (lane == 0) s_w[w] = (uint32_t)wave_total;
-  __syncthreads();
+  lds_barrier();
   int base = 0, total = 0;
 #pragma unroll
   for (int i = 0; i < NW; ++i) { const int c = (int)s_w[i]; base += i < w ? c : 0; total += c; }
@@ -110,7 +110,7 @@ __device__ __forceinline__ bool select_pivot(const float4 (&v)[PIVOT_NV4], int K
   const int n = total;
   const int n4 = (n + 3) >> 2;
   if (tid < 4 && n + tid < 4 * n4) { s_key[n + tid] = 0u; s_idx[n + tid] = 0x7fffffff; }   // pad to a multiple of four
-  __syncthreads();
+  lds_barrier();
   // exact rank by (key desc, id asc): four lanes per entry, each comparing against a quarter of
   // the list (uint4 reads), partial ranks summed inside the quad; the rank is the output slot
   const int part = tid & 3;
@@ -244,9 +244,9 @@ __device__ __forceinline__ float block_max_f(float m, float* s_red /*[BLOCK / 64
   constexpr int NW = BLOCK / 64;
   m = row16_max(m);
   m = fmaxf(fmaxf(lane_f(m, 0), lane_f(m, 16)), fmaxf(lane_f(m, 32), lane_f(m, 48)));
-  __syncthreads();
+  lds_barrier();
   if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = m;
-  __syncthreads();
+  lds_barrier();
   float M = s_red[0];
 #pragma unroll
   for (int i = 1; i < NW; ++i) M = fmaxf(M, s_red[i]);
@@ -258,9 +258,9 @@ __device__ __forceinline__ double block_sum_d(float sum, double* s_d /*[BLOCK / 
   sum = row16_sum(sum);
   const double ws = ((double)lane_f(sum, 0) + (double)lane_f(sum, 16)) +
                     ((double)lane_f(sum, 32) + (double)lane_f(sum, 48));
-  __syncthreads();
+  lds_barrier();
   if ((threadIdx.x & 63) == 0) s_d[threadIdx.x >> 6] = ws;
-  __syncthreads();
+  lds_barrier();
   double tot = 0.0;
 #pragma unroll
   for (int i = 0; i < NW; ++i) tot += s_d[i];
@@ -433,7 +433,8 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
       g_cid[i] = id;
     }
   }
-  __syncthreads();                                         // candidates and f terms visible to the whole block
+  // candidates and f terms visible to the whole block (large K: the ids are read back from global memory)
+  if (smallk) lds_barrier(); else __syncthreads();
   TRACE_POINT(p, grp, 3);
 
   // ---------------- 3. prefix scores ----------------------------------------------------
@@ -498,20 +499,20 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
   if (e2) {
     // Frame T is one of the R frames and there X_T is simply the best full prefix score of the
     // extensions, which is already known: most eligible hypotheses fail this test and skip the rest.
-    __syncthreads();                                       // s_inc / g_inc of all candidates written
+    if (smallk) lds_barrier(); else __syncthreads();       // s_inc / g_inc of all candidates written
     float xt = -3.0e38f;
     for (int c = tid; c < K; c += BLOCK) xt = fmaxf(xt, canon0(smallk ? s_inc[c] : g_inc[c]));
     xt = row16_max(xt);
     xt = fmaxf(fmaxf(lane_f(xt, 0), lane_f(xt, 16)), fmaxf(lane_f(xt, 32), lane_f(xt, 48)));
     if ((tid & 63) == 0) s_e2w[tid >> 6] = xt;
     if (tid == 0) s_e2w[BLOCK / 64] = (rs <= T && re >= T) ? canon0(lae(eos_n, eos_b)) : LOG0F;
-    __syncthreads();
+    lds_barrier();
     float XT = s_e2w[0];
 #pragma unroll
     for (int w2 = 1; w2 < BLOCK / 64; ++w2) XT = fmaxf(XT, s_e2w[w2]);
     const float ET = s_e2w[BLOCK / 64];
     const bool maybe = (ET > LOG0_CLASS) && (XT < LOG0_CLASS || ET > XT);
-    __syncthreads();                                       // s_e2w is reused below
+    lds_barrier();                                         // s_e2w is reused below
     if (maybe) {
     // running prefix score of every extension at frame T-R: the same sum with the last R frames
     // cut off (second pass over the columns; they are still in cache)
@@ -555,7 +556,7 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
       }
     }
     if (tid == 0) s_nvalid = 1;                            // reused as the "all frames passed" flag
-    __syncthreads();
+    lds_barrier();
     if (tid < R) {
       const int t = T - R + 1 + tid;
       const float Et = canon0(lae(gn[t], gb[t]));
@@ -566,11 +567,11 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
       const bool gt = (Et > LOG0_CLASS) && (X < LOG0_CLASS || Et > X);
       if (!gt) s_nvalid = 0;                               // every writer stores the same value
     }
-    __syncthreads();
+    lds_barrier();
     fire = s_nvalid;
     }                                                      // maybe
     if (tid == 0) p.stopped[grp] = fire;
-    __syncthreads();                                       // s_nvalid is reset below
+    lds_barrier();                                         // s_nvalid is reset below
   } else if (tid == 0) {
     p.stopped[grp] = 0;
   }
@@ -578,7 +579,7 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
   if (smallk) {
     // rank by (joint desc, token asc)
     if (tid == 0) s_nvalid = 0;
-    __syncthreads();                                       // s_J complete
+    lds_barrier();                                         // s_J complete
     if (!fire) {
       const int part = tid & 3;
       for (int e0 = 0; e0 < K; e0 += BLOCK / 4) {          // four lanes per candidate
@@ -602,7 +603,7 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
         }
       }
     }
-    __syncthreads();
+    lds_barrier();
     if (tid == 0) p.grp_n[grp] = fire ? 0 : min(s_nvalid, p.Wb);
   }
   TRACE_POINT(p, grp, 5);

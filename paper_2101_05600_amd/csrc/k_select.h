@@ -59,6 +59,144 @@ __device__ __forceinline__ ArgMax wave_argmax(ArgMax x) {
   return x;
 }
 
+// Forward variables of one new hypothesis (parent slot `par` extended by `tok`) over the
+// parent's window, by one wave: two scans of affine maps in the (logaddexp, +) semiring, 128
+// frames per pass (each lane owns two consecutive frames, composes their two maps, the wave
+// scans the composed maps, and the lane then replays its own two frames).  Writes the new
+// state (re-based on the child's own prefix score) into slot n of the other buffer and returns
+// tau / tau~ (first argmax from the parent's tau on; the parent's values if nothing is finite).
+struct SurvivorIn {
+  int par, tok, s, en, rs, re, ptau, ptau_end, plast;
+  float inc;
+};
+__device__ __forceinline__ void wave_survivor(const Params& p, int u, int n, int cur, const SurvivorIn& in,
+                                              int& arg_n, int& arg_b) {
+  const int lane = threadIdx.x & 63;
+  const size_t h0 = (size_t)u * p.Wb;
+  const size_t hp = h0 + in.par;
+  const float* xu = p.xT + (size_t)u * p.V * p.Tp;
+  const float* x0 = xu + (size_t)p.blank_id * p.Tp;
+  const float* xc = xu + (size_t)in.tok * p.Tp;
+  const float* pgn = p.gn[cur] + hp * p.Tp;
+  const float* pgb = p.gb[cur] + hp * p.Tp;
+  float* cgn = p.gn[cur ^ 1] + (h0 + n) * p.Tp;
+  float* cgb = p.gb[cur ^ 1] + (h0 + n) * p.Tp;
+  const int s = in.s, en = in.en, rs = in.rs, re = in.re;
+  const float inc = in.inc;
+  const bool rep = (in.tok == in.plast);
+  const int lo = max(s, in.ptau);
+  float carry_n = LOG0F, carry_b = LOG0F;
+  float best_n = LOG0F, best_b = LOG0F;
+  arg_n = in.ptau; arg_b = in.ptau_end;
+  for (int base = s; base <= en; base += 128) {
+    const int ta = base + 2 * lane, tb = ta + 1;
+    const bool va = ta <= en, vb = tb <= en;
+    const int tac = min(ta, en), tbc = min(tb, en);      // clamped: loads are unconditional
+    const float gna = pgn[max(tac - 1, 0)], gba = pgb[max(tac - 1, 0)];
+    const float gnb = pgn[tbc - 1], gbb = pgb[tbc - 1];
+    const float xa = xc[tac], xb = xc[tbc], x0a = x0[tac], x0b = x0[tbc];
+    float fa = LOG0F, fb = LOG0F;
+    if (ta - 1 >= rs && ta - 1 <= re) fa = rep ? gba : lae(gna, gba);
+    if (tb - 1 >= rs && tb - 1 <= re) fb = rep ? gbb : lae(gnb, gbb);
+    Aff ma, mb;                                          // n_t = (n_{t-1} (+) f_t) + x_t(c)
+    ma.a = va ? xa : 0.0f; ma.b = va ? fa + xa : LOG0F;
+    mb.a = vb ? xb : 0.0f; mb.b = vb ? fb + xb : LOG0F;
+    Aff P = wave_scan_aff(aff_then(ma, mb));
+    Aff E;                                               // maps of all earlier lanes
+    E.a = dpp_f<0x138, 0xf>(0.0f, P.a); E.b = dpp_f<0x138, 0xf>(LOG0F, P.b);
+    const float n_in = lae(E.a + carry_n, E.b);
+    const float na = lae(n_in + ma.a, ma.b);
+    const float nb = lae(na + mb.a, mb.b);
+    ma.a = va ? x0a : 0.0f; ma.b = va ? n_in + x0a : LOG0F;   // b_t = (n_{t-1} (+) b_{t-1}) + x_t(blank)
+    mb.a = vb ? x0b : 0.0f; mb.b = vb ? na + x0b : LOG0F;
+    P = wave_scan_aff(aff_then(ma, mb));
+    E.a = dpp_f<0x138, 0xf>(0.0f, P.a); E.b = dpp_f<0x138, 0xf>(LOG0F, P.b);
+    const float b_in = lae(E.a + carry_b, E.b);
+    const float ba = lae(b_in + ma.a, ma.b);
+    const float bb = lae(ba + mb.a, mb.b);
+    carry_n = lane_f(nb, 63); carry_b = lane_f(bb, 63);
+    // re-base on the child's own prefix score and store
+    const float rna = (na < LOG0_CLASS) ? LOG0F : na - inc, rnb = (nb < LOG0_CLASS) ? LOG0F : nb - inc;
+    const float rba = (ba < LOG0_CLASS) ? LOG0F : ba - inc, rbb = (bb < LOG0_CLASS) ? LOG0F : bb - inc;
+    if (va) { cgn[ta] = rna; cgb[ta] = rba; }
+    if (vb) { cgn[tb] = rnb; cgb[tb] = rbb; }
+    // first argmax over t >= lo
+    const float ca = (va && ta >= lo) ? rna : LOG0F, cb = (vb && tb >= lo) ? rnb : LOG0F;
+    const float da = (va && ta >= lo) ? rba : LOG0F, db = (vb && tb >= lo) ? rbb : LOG0F;
+    ArgMax xn, xb2;
+    xn.v = cb > ca ? cb : ca; xn.t = cb > ca ? tb : ta;
+    xb2.v = db > da ? db : da; xb2.t = db > da ? tb : ta;
+    xn = wave_argmax(xn); xb2 = wave_argmax(xb2);
+    if (xn.v > LOG0_CLASS && xn.v > best_n) { best_n = xn.v; arg_n = xn.t; }
+    if (xb2.v > LOG0_CLASS && xb2.v > best_b) { best_b = xb2.v; arg_b = xb2.t; }
+  }
+}
+
+// Ended set and ENDDETECT of one utterance, by one wave (lane j = old slot j).  `mine`: slot j
+// held a live hypothesis; je / stp / tau_j / cells_j: its eos joint score, eos-run stop, tau and
+// prefix-score terms of this step.  st_* / ring_*: the utterance's state as loaded by lane 0
+// (scalars) and lanes m < M (ring entries).  Writes the state back, the two per-old-slot
+// outputs and the work counters; returns whether the utterance finishes at this step.
+__device__ __forceinline__ bool wave_ended_set(const Params& p, int u, int l, int T, int lmax_u, bool has_best,
+                                               double best, int n_new, bool mine, double je_in, int stp_in,
+                                               int tau_j, long long cells_j, double st_best, int st_n,
+                                               int st_cnt, double ring_sc, int ring_tag) {
+  const int lane = threadIdx.x & 63, Wb = p.Wb;
+  const size_t h0 = (size_t)u * Wb;
+  UttState* us = p.utt + u;
+  const bool forced = (l >= lmax_u);
+  const double je = mine ? je_in : LOG0D;
+  const int stp = mine ? stp_in : 0;
+  const bool je_ok = je > (double)LOG0_CLASS;
+  const bool added = mine && (forced || stp || (je_ok && (!has_best || je > best)));
+  long long cells = mine ? cells_j : 0;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) cells += __shfl_xor(cells, o);
+  const int ngroups = __popcll(__ballot(mine));
+  const int n_add = __popcll(__ballot(added));
+  const int n_tauT = __popcll(__ballot(added && tau_j == T));
+  // best newly ended entry: largest score, lowest slot among equals (the one added first)
+  double bje = added ? je : -1.0e300; int bj = added ? lane : 0x7fffffff;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const double ov = __shfl_xor(bje, o); const int oj = __shfl_xor(bj, o);
+    if (ov > bje || (ov == bje && oj < bj)) { bje = ov; bj = oj; }
+  }
+  if (lane < Wb) { p.out_eos_added[h0 + lane] = (uint8_t)added; p.out_stopped[h0 + lane] = (uint8_t)stp; }
+  const int n_before = __shfl(st_n, 0);
+  const int n_ended = n_before + n_add;
+  const int cnt = __shfl(st_cnt, 0) + n_tauT;
+  double ybest = __shfl(st_best, 0);
+  const bool new_best = n_add > 0 && (n_before == 0 || bje > ybest);
+  if (new_best) ybest = bje;
+  // ring of the best ended score per length (slot = length % M)
+  const int M = p.end_m;
+  const bool ring_upd = (lane == (l % M)) && n_add > 0;
+  if (ring_upd) { ring_tag = l; ring_sc = bje; }
+  bool fin = forced || n_new == 0;
+  if (!fin && n_ended > 0) {
+    if (p.end_flags & 1) {                       // Eq. (4)
+      const bool counts = lane < M && ring_tag >= 1 && ring_tag > l - M && ring_tag <= l &&
+                          (ring_sc - ybest < (double)p.end_d);
+      if (__popcll(__ballot(counts)) == M) fin = true;
+    }
+    if (!fin && (p.end_flags & 2) && cnt > p.end_c) fin = true;   // Algorithm 3
+  }
+  if (ring_upd) { us->ring_tag[lane] = ring_tag; us->ring_score[lane] = ring_sc; }
+  if (lane == 0) {
+    us->n_ended = n_ended; us->cnt_tau_T = cnt;
+    if (new_best) { us->best_score = ybest; us->best_step = l; us->best_slot = bj; }
+    if (fin) {
+      us->finished_step = l;
+      p.finished[u] = 1;
+      atomicAdd(p.n_finished, 1);
+    }
+    p.cells[u] += (unsigned long long)cells;
+    p.groups[u] += (unsigned long long)ngroups;
+  }
+  return fin;
+}
+
 template <int BLOCK>
 __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
   constexpr int NW = BLOCK / 64;
@@ -115,7 +253,7 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
     }
   }
   if (tid < MAX_BEAM) s_sel[tid] = -1;
-  __syncthreads();
+  lds_barrier();
   TRACE_POINT(p, u, 9);
   // every thread sums the list lengths itself (independent LDS reads, no serial section)
   int ne = 0;
@@ -141,7 +279,7 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
       }
     }
   }
-  __syncthreads();
+  lds_barrier();
   // ---- rank (total order: joint desc, parent slot asc, candidate index asc = token asc) -----
   // eight lanes per entry, each comparing against an eighth of the list
   for (int e0 = 0; e0 < ne; e0 += BLOCK / 8) {
@@ -162,7 +300,7 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
     rank += __shfl_xor(rank, 4);
     if (part == 0 && have && rank < Wb) s_sel[rank] = e;
   }
-  __syncthreads();
+  lds_barrier();
 
   TRACE_POINT(p, u, 10);
   // ---- ended set, end detection: wave 0, lane j = old slot j ---------------------------------
@@ -170,131 +308,27 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
   if (w == 0) {
     const bool has_best = ne > 0;
     const double best = has_best ? s_J[s_sel[0]] : LOG0D;
-    const bool forced = (l >= lmax_u);
-    const bool mine = lane < Wb && o_live[lane];
-    const double je = mine ? o_je[lane] : LOG0D;
-    const int stp = mine ? o_stp[lane] : 0;
-    const bool je_ok = je > (double)LOG0_CLASS;
-    const bool added = mine && (forced || stp || (je_ok && (!has_best || je > best)));
-    long long cells = mine ? o_cells[lane] : 0;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) cells += __shfl_xor(cells, o);
-    const int ngroups = __popcll(__ballot(mine));
-    const int n_add = __popcll(__ballot(added));
-    const int n_tauT = __popcll(__ballot(added && o_tau[lane < Wb ? lane : 0] == T));
-    // best newly ended entry: largest score, lowest slot among equals (the one added first)
-    double bje = added ? je : -1.0e300; int bj = added ? lane : 0x7fffffff;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      const double ov = __shfl_xor(bje, o); const int oj = __shfl_xor(bj, o);
-      if (ov > bje || (ov == bje && oj < bj)) { bje = ov; bj = oj; }
-    }
-    if (lane < Wb) { p.out_eos_added[h0 + lane] = (uint8_t)added; p.out_stopped[h0 + lane] = (uint8_t)stp; }
-    const int n_before = __shfl(st_n, 0);
-    const int n_ended = n_before + n_add;
-    const int cnt = __shfl(st_cnt, 0) + n_tauT;
-    double ybest = __shfl(st_best, 0);
-    const bool new_best = n_add > 0 && (n_before == 0 || bje > ybest);
-    if (new_best) ybest = bje;
-    // ring of the best ended score per length (slot = length % M)
-    const int M = p.end_m;
-    const bool ring_upd = (lane == (l % M)) && n_add > 0;
-    if (ring_upd) { ring_tag = l; ring_sc = bje; }
-    bool fin = forced || n_new == 0;
-    if (!fin && n_ended > 0) {
-      if (p.end_flags & 1) {                       // Eq. (4)
-        const bool counts = lane < M && ring_tag >= 1 && ring_tag > l - M && ring_tag <= l &&
-                            (ring_sc - ybest < (double)p.end_d);
-        if (__popcll(__ballot(counts)) == M) fin = true;
-      }
-      if (!fin && (p.end_flags & 2) && cnt > p.end_c) fin = true;   // Algorithm 3
-    }
-    if (ring_upd) { us->ring_tag[lane] = ring_tag; us->ring_score[lane] = ring_sc; }
-    if (lane == 0) {
-      us->n_ended = n_ended; us->cnt_tau_T = cnt;
-      if (new_best) { us->best_score = ybest; us->best_step = l; us->best_slot = bj; }
-      if (fin) {
-        us->finished_step = l;
-        p.finished[u] = 1;
-        atomicAdd(p.n_finished, 1);
-      }
-      p.cells[u] += (unsigned long long)cells;
-      p.groups[u] += (unsigned long long)ngroups;
-      s_fin = fin ? 1 : 0;
-    }
+    const int j = lane < Wb ? lane : 0;
+    const bool mine = lane < Wb && o_live[j];
+    const bool fin = wave_ended_set(p, u, l, T, lmax_u, has_best, best, n_new, mine, o_je[j], o_stp[j], o_tau[j],
+                                    o_cells[j], st_best, st_n, st_cnt, ring_sc, ring_tag);
+    if (lane == 0) s_fin = fin ? 1 : 0;
   }
   TRACE_POINT(p, u, 11);
 
   TRACE_POINT(p, u, 12);
   // ---- forward variables of the new hypotheses --------------------------------------------
-  const float* xu = p.xT + (size_t)u * p.V * p.Tp;
-  const float* x0 = xu + (size_t)p.blank_id * p.Tp;
   // (wave 0 is busy with the ended set above; the other waves take the survivors at once.  A
   // finished utterance's new state is computed too but never used: its slots are marked dead.)
   const size_t trie_l = ((size_t)l * p.U + u) * Wb;
   for (int n = w - 1; n >= 0 && n < n_new; n += NW - 1) {
-    const int e = s_sel[n], par = s_par[e], tok = s_tok[e];
-    const size_t hp = h0 + par;
-    const float inc = s_inc[e];
-    const int s = o_ws[par], en = o_we[par];
-    const int rs = o_rs[par], re = o_re[par];
-    const int ptau = o_tau[par], ptau_end = o_tau_end[par];
-    const bool rep = (tok == o_last[par]);
-    const float* pgn = p.gn[cur] + hp * p.Tp;
-    const float* pgb = p.gb[cur] + hp * p.Tp;
-    float* cgn = p.gn[nxt] + (h0 + n) * p.Tp;
-    float* cgb = p.gb[nxt] + (h0 + n) * p.Tp;
-    const float* xc = xu + (size_t)tok * p.Tp;
-    const int lo = max(s, ptau);
-    float carry_n = LOG0F, carry_b = LOG0F;
-    float best_n = LOG0F, best_b = LOG0F;
-    int arg_n = ptau, arg_b = ptau_end;
-    // 128 frames per pass: each lane owns two consecutive frames, composes their two affine
-    // maps, the wave scans the composed maps, and the lane then replays its own two frames
-    for (int base = s; base <= en; base += 128) {
-      const int ta = base + 2 * lane, tb = ta + 1;
-      const bool va = ta <= en, vb = tb <= en;
-      const int tac = min(ta, en), tbc = min(tb, en);      // clamped: loads are unconditional
-      const float gna = pgn[max(tac - 1, 0)], gba = pgb[max(tac - 1, 0)];
-      const float gnb = pgn[tbc - 1], gbb = pgb[tbc - 1];
-      const float xa = xc[tac], xb = xc[tbc], x0a = x0[tac], x0b = x0[tbc];
-      float fa = LOG0F, fb = LOG0F;
-      if (ta - 1 >= rs && ta - 1 <= re) fa = rep ? gba : lae(gna, gba);
-      if (tb - 1 >= rs && tb - 1 <= re) fb = rep ? gbb : lae(gnb, gbb);
-      Aff ma, mb;                                          // n_t = (n_{t-1} (+) f_t) + x_t(c)
-      ma.a = va ? xa : 0.0f; ma.b = va ? fa + xa : LOG0F;
-      mb.a = vb ? xb : 0.0f; mb.b = vb ? fb + xb : LOG0F;
-      Aff P = wave_scan_aff(aff_then(ma, mb));
-      Aff E;                                               // maps of all earlier lanes
-      E.a = dpp_f<0x138, 0xf>(0.0f, P.a); E.b = dpp_f<0x138, 0xf>(LOG0F, P.b);
-      const float n_in = lae(E.a + carry_n, E.b);
-      const float na = lae(n_in + ma.a, ma.b);
-      const float nb = lae(na + mb.a, mb.b);
-      ma.a = va ? x0a : 0.0f; ma.b = va ? n_in + x0a : LOG0F;   // b_t = (n_{t-1} (+) b_{t-1}) + x_t(blank)
-      mb.a = vb ? x0b : 0.0f; mb.b = vb ? na + x0b : LOG0F;
-      P = wave_scan_aff(aff_then(ma, mb));
-      E.a = dpp_f<0x138, 0xf>(0.0f, P.a); E.b = dpp_f<0x138, 0xf>(LOG0F, P.b);
-      const float b_in = lae(E.a + carry_b, E.b);
-      const float ba = lae(b_in + ma.a, ma.b);
-      const float bb = lae(ba + mb.a, mb.b);
-      carry_n = lane_f(nb, 63); carry_b = lane_f(bb, 63);
-      // re-base on the child's own prefix score and store
-      const float rna = (na < LOG0_CLASS) ? LOG0F : na - inc, rnb = (nb < LOG0_CLASS) ? LOG0F : nb - inc;
-      const float rba = (ba < LOG0_CLASS) ? LOG0F : ba - inc, rbb = (bb < LOG0_CLASS) ? LOG0F : bb - inc;
-      if (va) { cgn[ta] = rna; cgb[ta] = rba; }
-      if (vb) { cgn[tb] = rnb; cgb[tb] = rbb; }
-      // first argmax over t >= lo
-      const float ca = (va && ta >= lo) ? rna : LOG0F, cb = (vb && tb >= lo) ? rnb : LOG0F;
-      const float da = (va && ta >= lo) ? rba : LOG0F, db = (vb && tb >= lo) ? rbb : LOG0F;
-      ArgMax xn, xb2;
-      xn.v = cb > ca ? cb : ca; xn.t = cb > ca ? tb : ta;
-      xb2.v = db > da ? db : da; xb2.t = db > da ? tb : ta;
-      xn = wave_argmax(xn); xb2 = wave_argmax(xb2);
-      const float vn = xn.v, vbv = xb2.v;
-      const int tn = xn.t, tbt = xb2.t;
-      if (vn > LOG0_CLASS && vn > best_n) { best_n = vn; arg_n = tn; }
-      if (vbv > LOG0_CLASS && vbv > best_b) { best_b = vbv; arg_b = tbt; }
-    }
+    const int e = s_sel[n], par = s_par[e];
+    SurvivorIn in;
+    in.par = par; in.tok = s_tok[e]; in.inc = s_inc[e];
+    in.s = o_ws[par]; in.en = o_we[par]; in.rs = o_rs[par]; in.re = o_re[par];
+    in.ptau = o_tau[par]; in.ptau_end = o_tau_end[par]; in.plast = o_last[par];
+    int arg_n, arg_b;
+    wave_survivor(p, u, n, cur, in, arg_n, arg_b);
     if (lane == 0) {
       p.h_tau[nxt][h0 + n] = arg_n; p.h_tau_end[nxt][h0 + n] = arg_b;
       p.out_tau[h0 + n] = arg_n; p.out_tau_end[h0 + n] = arg_b;
@@ -302,7 +336,7 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
       s_ntau[n] = arg_n; s_ntau_end[n] = arg_b;
     }
   }
-  __syncthreads();
+  lds_barrier();                       // (the survivors' state stores stay in flight)
   const bool fin = s_fin != 0;
   // ---- new beam: records, outputs, back-pointers ------------------------------------------
   for (int n = tid; n < Wb; n += BLOCK) {
@@ -331,4 +365,160 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
   }
 
   TRACE_POINT(p, u, 13);
+}
+
+// Split form of the select kernel: one work-group per (utterance, new beam slot n), used
+// whenever no state is shared across utterances (per-hypothesis windows).  Every work-group of
+// an utterance ranks the utterance's Wb * Wb list entries itself (the lists are small, the
+// ranking is cheaper than a second launch), wave 0 then evaluates the forward variables of
+// new hypothesis n and writes its record; in the work-group of slot 0, wave 1 meanwhile
+// updates the ended set, runs ENDDETECT and writes what belongs to the utterance as a whole
+// (finished flag, live flags of all slots, the per-old-slot outputs, work counters).  The
+// survivors of one utterance so run on Wb compute units instead of sharing one.
+// Within a launch the work-groups of an utterance only read what the others do not write:
+// the utterance state is read by slot 0's work-group alone, and "finished before this step"
+// is taken from the step number at which the utterance finished (0 or the current step both
+// mean no).
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void k_select_split(Params p, int l, int cur) {
+  constexpr int MAXE = MAX_BEAM * MAX_BEAM;
+  __shared__ double s_J[MAXE];
+  __shared__ __align__(16) unsigned long long s_key[MAXE + 8];
+  __shared__ int s_tok[MAXE];
+  __shared__ float s_inc[MAXE], s_att[MAXE];
+  __shared__ int o_live[MAX_BEAM], o_n[MAX_BEAM], o_stp[MAX_BEAM], o_tau[MAX_BEAM], o_tau_end[MAX_BEAM];
+  __shared__ int o_rs[MAX_BEAM], o_re[MAX_BEAM], o_last[MAX_BEAM], o_ws[MAX_BEAM], o_we[MAX_BEAM];
+  __shared__ long long o_cells[MAX_BEAM];
+  __shared__ double o_je[MAX_BEAM], o_hatt[MAX_BEAM], o_off[MAX_BEAM];
+  __shared__ int s_pick[2];                // entry ranked n, entry ranked 0
+
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int Wb = p.Wb;
+  const int u = blockIdx.x / Wb, n = blockIdx.x - u * Wb;
+  UttState* us = p.utt + u;
+  const int fs = us->finished_step;
+  if (fs != 0 && fs < l) return;           // outputs of a finished utterance were settled when it finished
+  const int nxt = cur ^ 1;
+  const size_t h0 = (size_t)u * Wb;
+  const bool lead = (n == 0);
+  if (lead) TRACE_POINT(p, u, 8);
+
+  // ---- round 1: every independent load ------------------------------------------------------
+  if (tid < Wb) {
+    const size_t h = h0 + tid;
+    o_live[tid] = p.h_live[cur][h]; o_n[tid] = p.grp_n[h]; o_stp[tid] = p.stopped[h];
+    o_tau[tid] = p.h_tau[cur][h]; o_tau_end[tid] = p.h_tau_end[cur][h];
+    o_rs[tid] = p.h_rs[cur][h]; o_re[tid] = p.h_re[cur][h]; o_last[tid] = p.h_last[cur][h];
+    o_ws[tid] = p.win_s[h]; o_we[tid] = p.win_e[h];
+    o_cells[tid] = p.grp_cells[h];
+    o_je[tid] = p.joint_eos[h]; o_hatt[tid] = p.h_att[cur][h]; o_off[tid] = p.h_off[cur][h];
+  }
+  const int T = p.lens[u];
+  const int lmax_u = p.lmax[u];
+  double st_best = LOG0D, ring_sc = LOG0D;
+  int st_n = 0, st_cnt = 0, ring_tag = -1;
+  if (lead && w == 1) {
+    if (lane == 0) { st_best = us->best_score; st_n = us->n_ended; st_cnt = us->cnt_tau_T; }
+    if (lane < p.end_m) { ring_sc = us->ring_score[lane]; ring_tag = us->ring_tag[lane]; }
+  }
+  // list entries i = j * Wb + r (group j's r-th best), each with a 64-bit sort key: the score as
+  // an order-preserving integer whose 10 lowest mantissa bits are replaced by the entry's
+  // position (earlier position = larger key).  One integer comparison then gives a strict total
+  // order: joint score descending, and among scores equal to within 2^-42 relative (far inside
+  // the tolerance to which scores are meaningful) parent slot, then token, ascending.  Entries
+  // past a list's length and the padding get keys below every score.
+  const int NE = Wb * Wb;
+  for (int i = tid; i < NE + 8; i += BLOCK) {
+    unsigned long long key = 0ull;
+    if (i < NE) {
+      const int j = i / Wb, r = i - j * Wb;
+      const size_t o = h0 * Wb + i;
+      const int nj = p.grp_n[h0 + j];
+      const double Jv = p.grp_J[o];
+      s_tok[i] = p.grp_tok[o]; s_inc[i] = p.grp_inc[o]; s_att[i] = p.grp_att[o];
+      s_J[i] = Jv;
+      const unsigned long long b = (unsigned long long)__double_as_longlong(Jv);
+      const unsigned long long k = (b >> 63) ? ~b : (b | 0x8000000000000000ull);
+      key = r < nj ? ((k & ~1023ull) | (unsigned long long)(1023 - i)) : (unsigned long long)(1023 - i) >> 1;
+    }
+    s_key[i] = key;
+  }
+  if (tid < 2) s_pick[tid] = -1;
+  lds_barrier();
+  if (lead) TRACE_POINT(p, u, 9);
+
+  // ---- rank (total order: joint desc, parent slot asc, token asc = position asc) -------------
+  // L lanes per entry, each comparing against every L-th pair of the list
+  int ne = 0;
+#pragma unroll 8
+  for (int j = 0; j < Wb; ++j) ne += o_n[j];
+  const int n_new = min(ne, Wb);
+  {
+    const int L = NE <= 64 ? 4 : (NE <= 128 ? 2 : 1);
+    const int part = tid & (L - 1);
+    const int quads = (NE + 3) >> 2;                       // (the padding holds zeros)
+    const ulonglong2* s_k2 = (const ulonglong2*)s_key;
+    for (int e0 = 0; e0 < NE; e0 += BLOCK / L) {
+      const int e = e0 + tid / L;
+      const unsigned long long me = s_key[min(e, NE)];
+      int rank = 0;
+      for (int q4 = part; q4 < quads; q4 += L) {            // four keys per trip, two independent reads
+        const ulonglong2 v = s_k2[2 * q4], v2 = s_k2[2 * q4 + 1];
+        rank += (v.x > me) + (v.y > me) + (v2.x > me) + (v2.y > me);
+      }
+      if (L >= 2) rank += dpp_i<0xB1, 0xf>(0, rank);       // quad_perm [1,0,3,2]
+      if (L == 4) rank += dpp_i<0x4E, 0xf>(0, rank);       // quad_perm [2,3,0,1]
+      if (part == 0 && e < NE && me > 1023ull) {
+        if (rank == n) s_pick[0] = e;
+        if (rank == 0) s_pick[1] = e;
+      }
+    }
+  }
+  lds_barrier();
+  if (lead) TRACE_POINT(p, u, 10);
+
+  const size_t trie_l = ((size_t)l * p.U + u) * Wb;
+  if (w == 0) {
+    // ---- new hypothesis n: forward variables, record, outputs, back-pointer -----------------
+    const size_t h = h0 + n;
+    if (n < n_new) {
+      const int e = s_pick[0], par = e / Wb;
+      SurvivorIn in;
+      in.par = par; in.tok = s_tok[e]; in.inc = s_inc[e];
+      in.s = o_ws[par]; in.en = o_we[par]; in.rs = o_rs[par]; in.re = o_re[par];
+      in.ptau = o_tau[par]; in.ptau_end = o_tau_end[par]; in.plast = o_last[par];
+      int arg_n, arg_b;
+      wave_survivor(p, u, n, cur, in, arg_n, arg_b);
+      if (lane == 0) {
+        p.h_tau[nxt][h] = arg_n; p.h_tau_end[nxt][h] = arg_b;
+        p.out_tau[h] = arg_n; p.out_tau_end[h] = arg_b;
+        p.trie_tau[trie_l + n] = arg_n;
+        p.out_parent[h] = par; p.out_token[h] = in.tok; p.out_score[h] = (float)s_J[e];
+        p.trie_parent[trie_l + n] = par; p.trie_token[trie_l + n] = in.tok;
+        p.h_last[nxt][h] = in.tok;
+        p.h_rs[nxt][h] = in.s; p.h_re[nxt][h] = in.en;
+        p.h_off[nxt][h] = o_off[par] + (double)in.inc;
+        p.h_att[nxt][h] = o_hatt[par] + (double)s_att[e];
+        p.h_joint[nxt][h] = s_J[e];
+      }
+    } else if (lane == 0) {
+      p.out_parent[h] = -1; p.out_token[h] = -1; p.out_score[h] = LOG0F;
+      p.out_tau[h] = 0; p.out_tau_end[h] = 0;
+      p.trie_parent[trie_l + n] = -1; p.trie_token[trie_l + n] = -1; p.trie_tau[trie_l + n] = 0;
+    }
+  } else if (lead && w == 1) {
+    // ---- the utterance as a whole: ended set, end detection, live flags ----------------------
+    const bool has_best = ne > 0;
+    const double best = has_best ? s_J[s_pick[1]] : LOG0D;
+    const int j = lane < Wb ? lane : 0;
+    const bool mine = lane < Wb && o_live[j];
+    const bool fin = wave_ended_set(p, u, l, T, lmax_u, has_best, best, n_new, mine, o_je[j], o_stp[j], o_tau[j],
+                                    o_cells[j], st_best, st_n, st_cnt, ring_sc, ring_tag);
+    if (lane < Wb) {
+      const int lv = (lane < n_new && !fin) ? 1 : 0;
+      p.out_live[h0 + lane] = (uint8_t)lv;
+      p.h_live[nxt][h0 + lane] = lv;
+    }
+  }
+  if (lead) TRACE_POINT(p, u, 13);
 }
