@@ -203,7 +203,7 @@ static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens)
   A(p.grp_n, UW); A(p.grp_J, UW * Wb); A(p.grp_ci, UW * Wb); A(p.grp_tok, UW * Wb);
   A(p.grp_inc, UW * Wb); A(p.grp_att, UW * Wb);
   A(p.ctc_eos, UW); A(p.joint_eos, UW); A(p.stopped, UW); A(p.grp_cells, UW);
-  A(p.utt, (size_t)U); A(p.finished, (size_t)U); A(p.cells, (size_t)U); A(p.groups, (size_t)U);
+  A(p.utt, (size_t)U); A(p.finished, (size_t)((U + 3) & ~3));   /* read as whole words by the score kernel */ A(p.cells, (size_t)U); A(p.groups, (size_t)U);
   A(p.n_finished, (size_t)1); A(p.union_win, (size_t)4);
   const size_t trie_n = (size_t)(h->l_cap_alloc + 1) * UW;
   A(p.trie_parent, trie_n); A(p.trie_token, trie_n); A(p.trie_tau, trie_n);
@@ -300,8 +300,13 @@ extern "C" int ctcbs_step(ctcbs_t* h, const float* d_att_logp, ctcbs_step_out_t*
     HIPCHK(hipGetLastError());
   }
   if (ev) HIPCHK(hipEventRecord(ev[1], h->stream));
-  if (!h->p.win_union) {
-    // per-hypothesis windows: nothing is shared across utterances, one work-group per new beam slot
+  // Small batches leave most compute units idle in the one-work-group-per-utterance form: there the
+  // split form (one work-group per new beam slot, each ranking the utterance's lists itself) is
+  // faster (measured: U=64 and U=128 at beam 10).  Large batches fill the chip either way and the
+  // Wb-fold repeated ranking only costs (U=256 at beam 20: three times slower).  The batch-union
+  // window needs the utterance's hypotheses in one place.
+  const bool split = !h->p.win_union && h->p.U * h->p.Wb <= 2048 && h->p.Wb <= 16;
+  if (split) {
     hipLaunchKernelGGL((k_select_split<256>), dim3(h->p.U * h->p.Wb), dim3(256), 0, h->stream, h->p, l, h->cur);
   } else switch (h->select_block) {
     case 256: hipLaunchKernelGGL((k_select<256>), dim3(h->p.U), dim3(256), 0, h->stream, h->p, l, h->cur); break;

@@ -268,7 +268,7 @@ __device__ __forceinline__ double block_sum_d(float sum, double* s_d /*[BLOCK / 
 }
 
 template <int BLOCK, int LPC, int CB, int IT>
-__global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const float* __restrict__ att,
+__global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, const float* __restrict__ att,
                                                  int l, int cur) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ uint32_t s_scan[BLOCK / 64 + 1];
@@ -284,6 +284,29 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
   const int K = p.K, V = p.V;
   const bool smallk = (K <= BLOCK);
 
+  // ---------------- first round of loads: the attention row and g's record -------------------
+  // Both are issued before the liveness test so that the row is already on its way while the
+  // record arrives (the step input holds a row for every slot, live or not; a dead slot's row
+  // is loaded and ignored).
+  const float* arow = att + (size_t)grp * V;
+  // attention row -> registers (restricted mode, rows that fit): PIVOT_NV4 float4 per lane, all
+  // in flight together (clamped, unconditional)
+  const bool in_regs = p.restricted && (V & 3) == 0 && (V >> 2) <= PIVOT_NV4 * BLOCK;
+  float4 arow_r[PIVOT_NV4];
+  if (in_regs) {
+    const float4* a4 = (const float4*)arow;
+    const int nv4 = V >> 2;
+#pragma unroll
+    for (int k = 0; k < PIVOT_NV4; ++k) arow_r[k] = a4[min(tid + k * BLOCK, nv4 - 1)];
+  }
+  // (the utterance's finished byte is fetched as part of its aligned word: a uniform word load
+  // can go through the scalar path, which is not ordered behind the row loads)
+  const uint32_t fin_word = ((const uint32_t*)p.finished)[u >> 2];
+  const int dead = (int)((fin_word >> (8 * (u & 3))) & 0xffu) | (p.h_live[cur][grp] == 0);
+  const int T = p.lens[u];
+  const int tau = p.h_tau[cur][grp], tau_end = p.h_tau_end[cur][grp];
+  const int rs = p.h_rs[cur][grp], re = p.h_re[cur][grp], last = p.h_last[cur][grp];
+  const double off = p.h_off[cur][grp], acum = p.h_att[cur][grp];
   // publish the count of finished utterances (as of the previous step) where the host can
   // read it without synchronising: one writer, plain store to device-mapped pinned memory
   if (grp == 0 && tid == 0) {
@@ -293,16 +316,6 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
     p.union_win[2 * ((l + 1) & 1)] = 0x7fffffff;
     p.union_win[2 * ((l + 1) & 1) + 1] = -1;
   }
-
-  // ---------------- first round of loads: g's record and its attention row ----------------
-  // (issued together, before the liveness test, so that they overlap; rows of dead slots are
-  // never dereferenced: their loads are skipped through the uniform early exit below only
-  // after the record arrived, the row loads are issued after it)
-  const int dead = p.finished[u] | (p.h_live[cur][grp] == 0);
-  const int T = p.lens[u];
-  const int tau = p.h_tau[cur][grp], tau_end = p.h_tau_end[cur][grp];
-  const int rs = p.h_rs[cur][grp], re = p.h_re[cur][grp], last = p.h_last[cur][grp];
-  const double off = p.h_off[cur][grp], acum = p.h_att[cur][grp];
   if (dead) {
     if (tid == 0) {
       p.grp_n[grp] = 0; p.win_s[grp] = 0; p.win_e[grp] = -1; p.stopped[grp] = 0;
@@ -320,20 +333,7 @@ __global__ __launch_bounds__(BLOCK) void k_score(Params p, ScoreSmem sm, const f
   int32_t* s_cid = (int32_t*)(s_J + Ks);                  // only touched when smallk
   float* s_inc = (float*)(smem + sm.off_small) + 3 * Ks;    // after J (2 words each) and cand_id
   float* s_av = s_inc + Ks;
-
-  const float* arow = att + (size_t)grp * V;
   int32_t* g_cid = p.cand_id + (size_t)grp * K;
-
-  // attention row -> registers (restricted mode, rows that fit): PIVOT_NV4 float4 per lane, all
-  // in flight together (clamped, unconditional)
-  const bool in_regs = p.restricted && (V & 3) == 0 && (V >> 2) <= PIVOT_NV4 * BLOCK;
-  float4 arow_r[PIVOT_NV4];
-  if (in_regs) {
-    const float4* a4 = (const float4*)arow;
-    const int nv4 = V >> 2;
-#pragma unroll
-    for (int k = 0; k < PIVOT_NV4; ++k) arow_r[k] = a4[min(tid + k * BLOCK, nv4 - 1)];
-  }
 
   // logits mode: the row holds unnormalised scores; log_softmax is folded in here (the order of
   // the ids is the same, only the values the scores use are shifted by the row's log-sum-exp)

@@ -396,8 +396,7 @@ __global__ __launch_bounds__(BLOCK) void k_select_split(Params p, int l, int cur
   const int Wb = p.Wb;
   const int u = blockIdx.x / Wb, n = blockIdx.x - u * Wb;
   UttState* us = p.utt + u;
-  const int fs = us->finished_step;
-  if (fs != 0 && fs < l) return;           // outputs of a finished utterance were settled when it finished
+  const int fs = us->finished_step;        // (tested after the first round of loads is on its way)
   const int nxt = cur ^ 1;
   const size_t h0 = (size_t)u * Wb;
   const bool lead = (n == 0);
@@ -444,6 +443,7 @@ __global__ __launch_bounds__(BLOCK) void k_select_split(Params p, int l, int cur
     s_key[i] = key;
   }
   if (tid < 2) s_pick[tid] = -1;
+  if (fs != 0 && fs < l) return;           // outputs of a finished utterance were settled when it finished
   lds_barrier();
   if (lead) TRACE_POINT(p, u, 9);
 
