@@ -27,7 +27,7 @@ struct ScoreSmem {
   // byte offsets into dynamic LDS, computed on the host
   int32_t off_work;   // union: uint32 hist[1 << RADIX_BITS] | { uint32 key[CAP + 4]; int32 idx[CAP + 4] }
   int32_t off_f;      // float F[wp_max], Fb[wp_max]
-  int32_t off_small;  // double J[Ks]; int32 cand_id[Ks]; float inc[Ks], att[Ks]  (Ks = K if K <= BLOCK else 0)
+  int32_t off_small;  // double J[Ks]; int32 cand_id[Ks]; float inc[Ks], att[Ks], pre[Ks]  (Ks = K if K <= BLOCK else 0)
   int32_t wp_max;     // floats available per F array
 };
 
@@ -333,6 +333,7 @@ __global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, cons
   int32_t* s_cid = (int32_t*)(s_J + Ks);                  // only touched when smallk
   float* s_inc = (float*)(smem + sm.off_small) + 3 * Ks;    // after J (2 words each) and cand_id
   float* s_av = s_inc + Ks;
+  float* s_pre = s_av + Ks;                                // eos-run rule: prefix score without the last R frames
   int32_t* g_cid = p.cand_id + (size_t)grp * K;
 
   // logits mode: the row holds unnormalised scores; log_softmax is folded in here (the order of
@@ -466,12 +467,29 @@ __global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, cons
       const float4* col = (const float4*)(xu + (size_t)id * p.Tp + t0);
       const float4* f4 = (const float4*)(s_F + ((id == last) ? sm.wp_max : 0));   // Fb follows F
       Lse a; a.m = LOG0F; a.s = 0.0f;
+      if (!e2) {
 #pragma unroll
-      for (int it = 0; it < IT; ++it) {
-        const int i = q + it * LPC;
-        if (i < n4) lse_add4(a, x[b][it], f4[i]);
+        for (int it = 0; it < IT; ++it) {
+          const int i = q + it * LPC;
+          if (i < n4) lse_add4(a, x[b][it], f4[i]);
+        }
+        for (int i = q + IT * LPC; i < n4; i += LPC) lse_add4(a, col[i], f4[i]);
+      } else {
+        // eos-run rule armed for g: also the same sum with the last R frames cut off (the running
+        // prefix score at frame T - R), from the same loads
+        Lse ap; ap.m = LOG0F; ap.s = 0.0f;
+#pragma unroll
+        for (int it = 0; it < IT; ++it) {
+          const int i = q + it * LPC;
+          if (i < n4) { lse_add4(a, x[b][it], f4[i]); lse_add4_upto(ap, x[b][it], f4[i], t0 + 4 * i, T - R); }
+        }
+        for (int i = q + IT * LPC; i < n4; i += LPC) {
+          const float4 xv = col[i];
+          lse_add4(a, xv, f4[i]); lse_add4_upto(ap, xv, f4[i], t0 + 4 * i, T - R);
+        }
+        const float pre = lse_finish<LPC>(ap);
+        if (q == 0) { if (smallk) s_pre[c] = pre; else p.cand_pre[(size_t)grp * K + c] = pre; }
       }
-      for (int i = q + IT * LPC; i < n4; i += LPC) lse_add4(a, col[i], f4[i]);
       const float inc = (W > 0) ? lse_finish<LPC>(a) : LOG0F;
       if (q == 0) {
         const float av = (smallk ? s_av[c] : arow[id]) - row_lse;
@@ -514,45 +532,39 @@ __global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, cons
     const bool maybe = (ET > LOG0_CLASS) && (XT < LOG0_CLASS || ET > XT);
     lds_barrier();                                         // s_e2w is reused below
     if (maybe) {
-    // running prefix score of every extension at frame T-R: the same sum with the last R frames
-    // cut off (second pass over the columns; they are still in cache)
-    const int t_cut = T - R;
-    for (int c = sg; c < K; c += NSG) {
-      const int id = smallk ? s_cid[c] : g_cid[c];
-      const float4* col = (const float4*)(xu + (size_t)id * p.Tp + t0);
-      const float4* f4 = (const float4*)(s_F + ((id == last) ? sm.wp_max : 0));
-      Lse ap; ap.m = LOG0F; ap.s = 0.0f;
-      for (int i = q; i < n4; i += LPC) lse_add4_upto(ap, col[i], f4[i], t0 + 4 * i, t_cut);
-      const float pre = lse_finish<LPC>(ap);
-      if (q == 0) p.cand_pre[(size_t)grp * K + c] = pre;
-    }
-    __syncthreads();                                       // cand_pre written by this block
-    float xmax[MAX_EOS_RUN];                               // per frame: best running prefix score seen by this lane
+    // the last R frames, eight at a time (few registers: this path is rare): every lane carries the
+    // running prefix score of its candidates from chunk to chunk through the pre array (each entry
+    // is only ever touched by one lane from here on) and keeps, per frame, the best score it has seen
+    constexpr int E2C = 8;
+    for (int k0 = 0; k0 < R; k0 += E2C) {
+      float xmax[E2C];
 #pragma unroll
-    for (int k = 0; k < MAX_EOS_RUN; ++k) xmax[k] = -3.0e38f;
-    for (int c = tid; c < K; c += BLOCK) {
-      const int id = smallk ? s_cid[c] : g_cid[c];
-      const float* colf = xu + (size_t)id * p.Tp;
-      const float* ff = s_F + ((id == last) ? sm.wp_max : 0);
-      float xv[MAX_EOS_RUN];
+      for (int k = 0; k < E2C; ++k) xmax[k] = -3.0e38f;
+      for (int c = tid; c < K; c += BLOCK) {
+        const int id = smallk ? s_cid[c] : g_cid[c];
+        const float* colf = xu + (size_t)id * p.Tp;
+        const float* ff = s_F + ((id == last) ? sm.wp_max : 0);
+        float xv[E2C];
 #pragma unroll
-      for (int k = 0; k < MAX_EOS_RUN; ++k) xv[k] = colf[min(T - R + 1 + k, T)];   // all loads in flight
-      float acc = p.cand_pre[(size_t)grp * K + c];
+        for (int k = 0; k < E2C; ++k) xv[k] = colf[min(T - R + 1 + k0 + k, T)];   // all loads in flight
+        float acc = smallk ? s_pre[c] : p.cand_pre[(size_t)grp * K + c];
 #pragma unroll
-      for (int k = 0; k < MAX_EOS_RUN; ++k) {
-        if (k < R) {
-          const int t = T - R + 1 + k;
-          acc = lae(acc, ff[t - t0] + xv[k]);
-          xmax[k] = fmaxf(xmax[k], canon0(acc));
+        for (int k = 0; k < E2C; ++k) {
+          if (k0 + k < R) {
+            const int t = T - R + 1 + k0 + k;
+            acc = lae(acc, ff[t - t0] + xv[k]);
+            xmax[k] = fmaxf(xmax[k], canon0(acc));
+          }
         }
+        if (smallk) s_pre[c] = acc; else p.cand_pre[(size_t)grp * K + c] = acc;
       }
-    }
 #pragma unroll
-    for (int k = 0; k < MAX_EOS_RUN; ++k) {                // max over the wave, one slot per wave and frame
-      if (k < R) {
-        float v = row16_max(xmax[k]);
-        v = fmaxf(fmaxf(lane_f(v, 0), lane_f(v, 16)), fmaxf(lane_f(v, 32), lane_f(v, 48)));
-        if ((tid & 63) == 0) s_e2w[(tid >> 6) * MAX_EOS_RUN + k] = v;
+      for (int k = 0; k < E2C; ++k) {                      // max over the wave, one slot per wave and frame
+        if (k0 + k < R) {
+          float v = row16_max(xmax[k]);
+          v = fmaxf(fmaxf(lane_f(v, 0), lane_f(v, 16)), fmaxf(lane_f(v, 32), lane_f(v, 48)));
+          if ((tid & 63) == 0) s_e2w[(tid >> 6) * MAX_EOS_RUN + k0 + k] = v;
+        }
       }
     }
     if (tid == 0) s_nvalid = 1;                            // reused as the "all frames passed" flag
