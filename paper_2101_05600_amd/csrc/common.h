@@ -23,9 +23,11 @@
 // shipped library).
 #ifdef CTCBS_TRACE
 #define TRACE_POINT(p, blk, i) do { if ((p).trace && threadIdx.x == 0) (p).trace[(size_t)(blk) * 16 + (i)] = wall_clock64(); } while (0)
+#define TRACE_RAW(ptr, i) do { if ((ptr) && threadIdx.x == 0) (ptr)[i] = wall_clock64(); } while (0)
 #define TRACE_POINT_T(p, blk, i, thr) do { if ((p).trace && threadIdx.x == (thr)) (p).trace[(size_t)(blk) * 16 + (i)] = wall_clock64(); } while (0)
 #else
 #define TRACE_POINT(p, blk, i) do { } while (0)
+#define TRACE_RAW(ptr, i) do { } while (0)
 #define TRACE_POINT_T(p, blk, i, thr) do { } while (0)
 #endif
 

@@ -241,7 +241,7 @@ static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens)
   sm.off_f = (int32_t)off;
   off += (size_t)2 * p.Tp * 4;                   // Tp is a multiple of 4: both arrays 16-byte aligned
   sm.off_small = (int32_t)off;
-  if (K <= h->score_block) off += (size_t)K * 24;
+  if (K <= h->score_block) off += (size_t)K * 32 + 8;
   sm.wp_max = p.Tp;
   h->score_smem_bytes = off;
   if (off > 160 * 1024) return CTCBS_EINVAL;

@@ -27,7 +27,7 @@ struct ScoreSmem {
   // byte offsets into dynamic LDS, computed on the host
   int32_t off_work;   // union: uint32 hist[1 << RADIX_BITS] | { uint32 key[CAP + 4]; int32 idx[CAP + 4] }
   int32_t off_f;      // float F[wp_max], Fb[wp_max]
-  int32_t off_small;  // double J[Ks]; int32 cand_id[Ks]; float inc[Ks], att[Ks], pre[Ks]  (Ks = K if K <= BLOCK else 0)
+  int32_t off_small;  // double J[Ks]; int32 cand_id[Ks]; float inc[Ks], att[Ks], pre[Ks]; double Jraw[Ks]  (Ks = K if K <= BLOCK else 0)
   int32_t wp_max;     // floats available per F array
 };
 
@@ -39,13 +39,16 @@ __device__ __forceinline__ float key_to_att(uint32_t k) {
 // Pivot path on the lane's register-resident row values (v[k] = ids 4 * (tid + k * BLOCK) ..+3;
 // excluded ids and ids past the row's end hold -inf).  Comparisons run on the floats
 // themselves; only each lane's maximum and the few collected values are turned into
-// order-preserving keys.  Returns false (uniformly) if the short list would overflow or, with
-// NaNs in the row, would hold fewer than K values.  Writes the K ids (and their attention
-// values) best first.
+// order-preserving keys.  Short-list entries are 64-bit: key in the upper word, ~id in the
+// lower, so that one integer comparison orders by (value descending, id ascending).
+// Returns false (uniformly) if the short list would overflow or, with NaNs in the row, would
+// hold fewer than K values.  Writes the K ids (and their attention values) best first.
+// s_ent: PIVOT_CAP + 4 entries; s_w: 2 * (BLOCK / 64) words.
 template <int BLOCK>
 __device__ __forceinline__ bool select_pivot(const float4 (&v)[PIVOT_NV4], int K, int blank_id, int eos_id,
-                                             uint32_t* s_key, int32_t* s_idx, uint32_t* s_w, bool use_lds,
-                                             int32_t* out_lds, float* out_att_lds, int32_t* out_g) {
+                                             unsigned long long* s_ent, uint32_t* s_w, bool use_lds,
+                                             int32_t* out_lds, float* out_att_lds, int32_t* out_g,
+                                             unsigned long long* tr) {
   constexpr int NW = BLOCK / 64;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const float ninf = -__builtin_huge_valf();
@@ -54,6 +57,7 @@ __device__ __forceinline__ bool select_pivot(const float4 (&v)[PIVOT_NV4], int K
   for (int k = 0; k < PIVOT_NV4; ++k)
     fmx = fmaxf(fmx, fmaxf(fmaxf(v[k].x, v[k].y), fmaxf(v[k].z, v[k].w)));
   const uint32_t lmax = att_key(fmx, -1, -2, -2);
+  TRACE_RAW(tr, 6);
   // r-th largest lane maximum of this wave, by bisection on the upper 16 key bits (sign,
   // exponent, 7 mantissa bits): stopping early only lowers the pivot, which stays valid
   const int r = (K + NW - 1) / NW;
@@ -63,6 +67,7 @@ __device__ __forceinline__ bool select_pivot(const float4 (&v)[PIVOT_NV4], int K
     const uint32_t trial = thr | (1u << bit);
     if (__popcll(__ballot(lmax >= trial)) >= r) thr = trial;
   }
+  TRACE_RAW(tr, 7);
   if (lane == 0) s_w[w] = thr;
   lds_barrier();
   uint32_t Lk = s_w[0];
@@ -70,69 +75,64 @@ __device__ __forceinline__ bool select_pivot(const float4 (&v)[PIVOT_NV4], int K
   for (int i = 1; i < NW; ++i) Lk = min(Lk, s_w[i]);
   // at least NW * r >= K values are >= L (as a float: -inf if no wave had r finite maxima)
   const float L = Lk <= att_key(ninf, -1, -2, -2) ? ninf : key_to_att(Lk);
-  // hits are rare (about 1.4 K of the whole row): per (k, j) slot one ballot says whether any
-  // lane of the wave holds one; empty slots cost a compare and a scalar test
-  int wave_total = 0;
+  // hits are rare (about 1.4 K of the whole row).  Every lane notes its own in a bit mask (bit
+  // 4k+j = component j of v[k]); a wave scan of the counts and the waves' totals give each lane the
+  // place of its first hit in the short list
+  uint32_t mask = 0;
 #pragma unroll
   for (int k = 0; k < PIVOT_NV4; ++k)
-    wave_total += __popcll(__ballot(v[k].x >= L)) + __popcll(__ballot(v[k].y >= L)) +
-                  __popcll(__ballot(v[k].z >= L)) + __popcll(__ballot(v[k].w >= L));
-  lds_barrier();                                         // s_w was read by everyone
-  if (lane == 0) s_w[w] = (uint32_t)wave_total;
+    mask |= ((uint32_t)(v[k].x >= L) << (4 * k)) | ((uint32_t)(v[k].y >= L) << (4 * k + 1)) |
+            ((uint32_t)(v[k].z >= L) << (4 * k + 2)) | ((uint32_t)(v[k].w >= L) << (4 * k + 3));
+  const int cnt = __popc(mask);
+  const int inc = (int)wave_incl_scan_u32((uint32_t)cnt, lane);
+  if (lane == 63) s_w[NW + w] = (uint32_t)inc;
   lds_barrier();
   int base = 0, total = 0;
 #pragma unroll
-  for (int i = 0; i < NW; ++i) { const int c = (int)s_w[i]; base += i < w ? c : 0; total += c; }
+  for (int i = 0; i < NW; ++i) { const int c = (int)s_w[NW + i]; base += i < w ? c : 0; total += c; }
   if (total > PIVOT_CAP || total < K) return false;
+  TRACE_RAW(tr, 14);
   const bool linf = (L == ninf);                           // then excluded ids (held as -inf) are hits too
+  int pos = base + inc - cnt;
+  // per float4 slot, one hit per trip (most lanes have none, hardly any more than one)
 #pragma unroll
   for (int k = 0; k < PIVOT_NV4; ++k) {
-    const float e[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const bool mine = e[j] >= L;
-      const unsigned long long m = __ballot(mine);
-      if (m != 0ull) {                                     // uniform over the wave
-        if (mine) {
-          const int id = 4 * (tid + k * BLOCK) + j;
-          const int pos = base + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
-                                        __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-          const uint32_t u = __float_as_uint(e[j]);
-          uint32_t key = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-          if (linf && (id == blank_id || id == eos_id)) key = 0u;   // below a genuine -inf
-          s_key[pos] = key;
-          s_idx[pos] = id;
-        }
-        base += __popcll(m);
-      }
+    uint32_t m4 = (mask >> (4 * k)) & 15u;
+    while (m4 != 0u) {
+      const int j = __ffs((int)m4) - 1;
+      m4 &= m4 - 1u;
+      const float val = j == 0 ? v[k].x : (j == 1 ? v[k].y : (j == 2 ? v[k].z : v[k].w));
+      const int id = 4 * (tid + k * BLOCK) + j;
+      const uint32_t u = __float_as_uint(val);
+      uint32_t key = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+      if (linf && (id == blank_id || id == eos_id)) key = 0u;   // below a genuine -inf
+      s_ent[pos++] = ((unsigned long long)key << 32) | (uint32_t)~id;
     }
   }
   const int n = total;
   const int n4 = (n + 3) >> 2;
-  if (tid < 4 && n + tid < 4 * n4) { s_key[n + tid] = 0u; s_idx[n + tid] = 0x7fffffff; }   // pad to a multiple of four
+  if (tid < 4 && n + tid < 4 * n4) s_ent[n + tid] = 0ull;    // pad to a multiple of four
   lds_barrier();
-  // exact rank by (key desc, id asc): four lanes per entry, each comparing against a quarter of
-  // the list (uint4 reads), partial ranks summed inside the quad; the rank is the output slot
+  TRACE_RAW(tr, 15);
+  // exact rank: four lanes per entry, each comparing against a quarter of the list (two entries
+  // per read), partial ranks summed inside the quad; the rank is the output slot
   const int part = tid & 3;
-  const uint4* s_key4 = (const uint4*)s_key;
-  const int4* s_idx4 = (const int4*)s_idx;
+  const ulonglong2* s_ent2 = (const ulonglong2*)s_ent;
   for (int e = tid >> 2; e < ((n + BLOCK / 4 - 1) / (BLOCK / 4)) * (BLOCK / 4); e += BLOCK / 4) {
-    const uint32_t me = e < n ? s_key[e] : 0u;
-    const int mid = e < n ? s_idx[e] : 0x7fffffff;
+    const unsigned long long me = e < n ? s_ent[e] : ~0ull;
     int rank = 0;
     for (int o4 = part; o4 < n4; o4 += 4) {
-      const uint4 kv = s_key4[o4];
-      const int4 d = s_idx4[o4];
-      rank += (kv.x > me) || (kv.x == me && d.x < mid);
-      rank += (kv.y > me) || (kv.y == me && d.y < mid);
-      rank += (kv.z > me) || (kv.z == me && d.z < mid);
-      rank += (kv.w > me) || (kv.w == me && d.w < mid);
+      const ulonglong2 a = s_ent2[2 * o4], b = s_ent2[2 * o4 + 1];
+      rank += (int)(a.x > me) + (int)(a.y > me) + (int)(b.x > me) + (int)(b.y > me);
     }
     rank += dpp_i<0xB1, 0xf>(0, rank);                     // quad_perm [1,0,3,2]
     rank += dpp_i<0x4E, 0xf>(0, rank);                     // quad_perm [2,3,0,1]
     if (part == 0 && e < n && rank < K) {
-      if (use_lds) { out_lds[rank] = mid; out_att_lds[rank] = key_to_att(me); }
-      out_g[rank] = mid;
+      const int mid = (int)~(uint32_t)me;
+      // (small K: the ids stay in LDS; the global copy is written with the scores at the end, so that
+      // no store is pending when the candidates' columns are fetched)
+      if (use_lds) { out_lds[rank] = mid; out_att_lds[rank] = key_to_att((uint32_t)(me >> 32)); }
+      else out_g[rank] = mid;
     }
   }
   return true;
@@ -202,7 +202,7 @@ __device__ __noinline__ void select_radix(const float* __restrict__ arow, int V,
     if (k == prefix) ++eq_before;
     if (take && pos < (uint32_t)K) {
       if (use_lds) { out_lds[pos] = i; out_att_lds[pos] = a; }
-      out_g[pos] = i;
+      else out_g[pos] = i;
       ++pos;
     }
   }
@@ -272,7 +272,7 @@ __global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, cons
                                                  int l, int cur) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ uint32_t s_scan[BLOCK / 64 + 1];
-  __shared__ uint32_t s_w[BLOCK / 64];
+  __shared__ uint32_t s_w[2 * (BLOCK / 64)];
   __shared__ uint32_t s_sel[2];
   __shared__ float s_e2w[(BLOCK / 64) * MAX_EOS_RUN + 1];
   __shared__ int s_nvalid;
@@ -334,6 +334,7 @@ __global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, cons
   float* s_inc = (float*)(smem + sm.off_small) + 3 * Ks;    // after J (2 words each) and cand_id
   float* s_av = s_inc + Ks;
   float* s_pre = s_av + Ks;                                // eos-run rule: prefix score without the last R frames
+  double* s_Jraw = (double*)(s_pre + Ks + (Ks & 1));       // joint score as computed (NaN kept), for the global copy
   int32_t* g_cid = p.cand_id + (size_t)grp * K;
 
   // logits mode: the row holds unnormalised scores; log_softmax is folded in here (the order of
@@ -422,8 +423,8 @@ __global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, cons
           if (jb == 3 || je == 3) arow_r[k].w = ninf;
         }
       }
-      ok = select_pivot<BLOCK>(arow_r, K, p.blank_id, p.eos_id, s_work, (int32_t*)(s_work + PIVOT_CAP + 4),
-                               s_w, smallk, s_cid, s_av, g_cid);
+      ok = select_pivot<BLOCK>(arow_r, K, p.blank_id, p.eos_id, (unsigned long long*)s_work,
+                               s_w, smallk, s_cid, s_av, g_cid, p.trace ? p.trace + (size_t)grp * 16 : nullptr);
     }
     if (!ok) select_radix<BLOCK>(arow, V, K, p.blank_id, p.eos_id, s_work, s_scan, s_sel, smallk, s_cid, s_av, g_cid);
   } else {
@@ -431,7 +432,7 @@ __global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, cons
     for (int i = tid; i < K; i += BLOCK) {
       const int id = full_v_id(i, lo_ex, hi_ex);
       if (smallk) { s_cid[i] = id; s_av[i] = arow[id]; }
-      g_cid[i] = id;
+      else g_cid[i] = id;
     }
   }
   // candidates and f terms visible to the whole block (large K: the ids are read back from global memory)
@@ -496,8 +497,11 @@ __global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, cons
         const bool valid = inc > LOG0_CLASS;
         const double ctc = valid ? off + (double)inc : LOG0D;
         const double J = valid ? lam * ctc + (1.0 - lam) * (double)av + jbase : LOG0D;
-        g_inc[c] = inc; g_catt[c] = av; g_ctc[c] = ctc; g_joint[c] = J;
-        if (smallk) { s_J[c] = (valid && J == J) ? J : LOG0D; s_inc[c] = inc; s_av[c] = av; }
+        // small K: scores stay in LDS for the ranking below, the per-candidate arrays in global memory
+        // (read back by ctcbs_peek only) are written from there at the very end, so that no store
+        // is pending while columns are still being fetched
+        if (smallk) { s_J[c] = (valid && J == J) ? J : LOG0D; s_inc[c] = inc; s_av[c] = av; s_Jraw[c] = J; }
+        else { g_inc[c] = inc; g_catt[c] = av; g_ctc[c] = ctc; g_joint[c] = J; }
       }
     }
   }
@@ -617,6 +621,12 @@ __global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, cons
     }
     lds_barrier();
     if (tid == 0) p.grp_n[grp] = fire ? 0 : min(s_nvalid, p.Wb);
+    for (int c = tid; c < K; c += BLOCK) {
+      const float inc = s_inc[c];
+      g_cid[c] = s_cid[c]; g_inc[c] = inc; g_catt[c] = s_av[c];
+      g_ctc[c] = inc > LOG0_CLASS ? off + (double)inc : LOG0D;
+      g_joint[c] = s_Jraw[c];
+    }
   }
   TRACE_POINT(p, grp, 5);
 }
