@@ -40,6 +40,10 @@ def parse():
     ap.add_argument("--inflight", type=int, default=1,
                     help="batches decoded concurrently, each on its own handle and stream (offline decoding "
                          "always has more batches queued); the default 1 is the headline figure")
+    ap.add_argument("--threads", type=int, default=1,
+                    help="host threads that drive the batches in flight (ctcbs_run_many)")
+    ap.add_argument("--no-offline", action="store_true",
+                    help="skip the extra 'offline' figure (8 batches in flight, 4 host threads) of the default run")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark line: decode the workload under the paper's window "
                          "settings (Table 'batch decoding': M1 = 5, M2 in {inf, 60, 40, 20}), the per-hypothesis "
@@ -164,33 +168,32 @@ class Batch:
             self.m.ctcbs_destroy(h)
         self.hs = []
 
-    def decode_many(self, n):
-        """n decodes of the same batch in flight at once, one handle and one stream each, their steps
-        enqueued round-robin by this one host thread."""
+    def decode_queue(self, n_slots, n_jobs, threads=1):
+        """n_jobs decodes of the same batch, n_slots of them in flight at once (one handle and one
+        stream each), driven by the library's own executor (ctcbs_run_queue: `threads` host threads
+        share the handles; every job re-ingests the posteriors with ctcbs_reset, is stepped with the
+        recorded rows served by ctcbs_att_replay, and ends with ctcbs_finalize)."""
         m, torch, U = self.m, self.torch, self.U
-        if not getattr(self, "hs", None):
-            self.streams = [torch.cuda.Stream() for _ in range(n)]
+        if len(getattr(self, "hs", [])) != n_slots:
+            for h in getattr(self, "hs", []):
+                m.ctcbs_destroy(h)
+            self.streams = [torch.cuda.Stream() for _ in range(n_slots)]
             self.hs = []
             for st in self.streams:
                 cfg = m.make_config(n_utt=self.U, t_max=self.t_max, poll_every=self.poll_every,
                                     stream=st.cuda_stream,
                                     **{k: v for k, v in self.w.items() if k not in ("n_utt", "stream")})
                 self.hs.append(m.ctcbs_create(cfg, self.d_ctc, self.lens))
-        else:
-            for h in self.hs:
+        results = [None] * n_jobs
+
+        def job_fn(job, slot, h, phase):
+            if phase == m.JOB_LOAD:
                 m.ctcbs_reset(h, self.d_ctc, self.lens)
-        outs = [m.StepOut() for _ in self.hs]
-        live = [True] * len(self.hs)
-        for step in range(1, self.l_cap + 1):
-            for i, h in enumerate(self.hs):
-                if not live[i]:
-                    continue
-                if m.ctcbs_step(h, self.att_ptr[min(step, self.n_steps) - 1], outs[i]) == m.DONE or \
-                        outs[i].n_finished == U:
-                    live[i] = False
-            if not any(live):
-                break
-        return [m.ctcbs_finalize(h, U, self.l_cap) for h in self.hs]
+            else:
+                results[job] = m.ctcbs_finalize(h, U, self.l_cap)
+        m.ctcbs_run_queue(self.hs, n_jobs, job_fn, replay=[self.att_ptr[:self.n_steps]] * n_jobs,
+                          n_threads=threads)
+        return results
 
 
 def cpu_baseline(batch, n_sample):
@@ -318,14 +321,12 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     if a.inflight > 1:
-        for _ in range(a.warmup):
-            b.decode_many(a.inflight)
+        b.decode_queue(a.inflight, a.inflight * max(a.warmup, 1), a.threads)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(a.steps):
-            many = b.decode_many(a.inflight)
+        many = b.decode_queue(a.inflight, a.inflight * a.steps, a.threads)
         torch.cuda.synchronize()
-        dt = (time.perf_counter() - t0) / a.inflight      # per decoded batch
+        dt = (time.perf_counter() - t0) / a.inflight      # a.steps batches per slot: dt / a.steps = per batch
         res = many[-1]
         for r in many:
             for x, y in zip(r[:3], ref[:3]):
@@ -371,13 +372,30 @@ def main():
                                f"M2={w['win_m2']}, end_flags={w['end_flags']}; one step = one whole "
                                f"batch decode (create + {b.n_steps} beam-search steps + finalize)",
                    "decode_steps": b.n_steps, "cells_per_decode": b.cells,
-                   "poll_every": a.poll_every, "batches_in_flight": a.inflight},
+                   "poll_every": a.poll_every, "batches_in_flight": a.inflight,
+                   "host_threads": a.threads if a.inflight > 1 else 1},
         "roofline": {"bound": "hbm", "kernel": "k_score", "achieved": ach, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": traffic,
                      "avg_launch_us": score_ms * 1e3 / max(n_prof, 1),
                      "algorithmic_bytes_per_launch": bytes_score / max(n_prof, 1),
                      "select_kernel_avg_us": select_ms * 1e3 / max(n_prof, 1)},
     }
+    if a.inflight == 1 and not a.no_offline:
+        # context, not the headline: a queue of copies of the same batch, 8 in flight (own handle and
+        # stream each), driven by the library's executor on 4 host threads -- what an offline run with a queue of
+        # batches gets out of the chip
+        nf, nt, reps = 8, 4, max(2, a.steps // 4)
+        b.decode_queue(nf, nf, nt)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        many = b.decode_queue(nf, nf * reps, nt)
+        torch.cuda.synchronize()
+        dto = (time.perf_counter() - t0) / (reps * nf)
+        for r in many:
+            for x, y in zip(r[:3], ref[:3]):
+                assert np.array_equal(x, y), "a concurrent decode did not reproduce the recorded decode"
+        line["offline"] = {"batches_in_flight": nf, "host_threads": nt, "ms_per_batch": dto * 1e3,
+                           "utterances_per_sec": b.U / dto, "value": b.cells / dto, "unit": "cells/s"}
     if not a.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(b, a.cpu_sample)
     print(json.dumps(line))

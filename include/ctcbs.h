@@ -195,6 +195,84 @@ enum {
 };
 int ctcbs_peek(ctcbs_t* h, int32_t what, void* h_dst, size_t bytes, size_t* need);
 
+/*
+ * ---- Offline scheduling around the path (host side; none of these touches a kernel) ----
+ *
+ * Hard segmentation by length (Sec. 3.3, second method; Sec. 4.4): cut a recording of
+ * n_frames frames into the fewest pieces no longer than max_len, with lengths as uniform as
+ * possible, the last piece included (they differ by at most one frame, longer ones first).
+ * Every piece is also >= min_len whenever n_frames allows it (always once n_frames >=
+ * min_len * max_len / (max_len - min_len)); a shorter recording still gets uniform pieces.
+ * h_len[0..*n_seg) receives the lengths in order.  CTCBS_ECAP (with *n_seg set) if cap is
+ * too small or h_len is NULL.
+ */
+int ctcbs_hard_segments(int64_t n_frames, int32_t min_len, int32_t max_len, int32_t* h_len,
+                        int32_t cap, int32_t* n_seg);
+
+/*
+ * Segments from voice-activity pieces (Sec. 4.4, first method; the detector itself is outside):
+ * consecutive pieces (lengths h_piece_len[0..n_pieces), in time order) are merged until a
+ * segment is at least min_len long; a segment longer than max_len is split again, uniformly,
+ * into the fewest parts that fit; what is left at the end stays a segment of its own.
+ * Output as for ctcbs_hard_segments.
+ */
+int ctcbs_merge_pieces(const int32_t* h_piece_len, int32_t n_pieces, int32_t min_len, int32_t max_len,
+                       int32_t* h_len, int32_t cap, int32_t* n_seg);
+
+/*
+ * Length-sorted batching (Sec. 4.2: segments are ordered by length so that a batch holds
+ * segments of similar length).  h_order[0..n) receives the segment indices longest first
+ * (equal lengths in input order); batch b is h_order[h_begin[b] .. h_begin[b+1]): at most
+ * max_utt segments and, if max_padded_frames > 0, at most that many frames after padding every
+ * segment of the batch to its longest (= first) one.  h_begin needs cap_batches + 1 entries;
+ * with h_begin NULL or too small the call only counts (*n_batches) and returns CTCBS_ECAP.
+ */
+int ctcbs_plan_batches(const int32_t* h_len, int32_t n, int32_t max_utt, int64_t max_padded_frames,
+                       int32_t* h_order, int32_t* h_begin, int32_t cap_batches, int32_t* n_batches);
+
+/*
+ * Where the attention rows of a step come from: called before every ctcbs_step of batch
+ * `index` with the 1-based step about to run and the previous step's views (NULL before the
+ * first), it must set *d_att to the [U][Wb][V] device rows for that step -- typically after
+ * enqueuing the decoder on the batch's stream -- and return 0, or a negative code to abort.
+ * With more than one thread in ctcbs_run_many it is called concurrently for different batches.
+ */
+typedef int (*ctcbs_att_fn)(void* user, int32_t index, int32_t step, const ctcbs_step_out_t* prev,
+                            const float** d_att);
+
+/*
+ * Decode n batches at once: handle hs[i] (created on a stream of its own for the kernels of
+ * different batches to overlap) is stepped until it reports CTCBS_DONE; n_threads host threads
+ * (the caller's included) share the batches, each stepping its own round-robin.  One batch of
+ * 64 utterances leaves most of the chip idle through its dependent phases; a few batches in
+ * flight fill it.  Results are read with ctcbs_finalize afterwards.  Returns the first error.
+ */
+int ctcbs_run_many(ctcbs_t* const* hs, int32_t n, ctcbs_att_fn fn, void* user, int32_t n_threads);
+
+/* A ready-made ctcbs_att_fn that replays recorded inputs: user = ctcbs_replay_t[n], entry i
+ * listing the device rows of batch i step by step (steps past n_steps get the last rows). */
+typedef struct {
+  const float* const* d_att;  /* [n_steps] device pointers, each [U][Wb][V]                    */
+  int32_t n_steps;
+} ctcbs_replay_t;
+int ctcbs_att_replay(void* user, int32_t index, int32_t step, const ctcbs_step_out_t* prev,
+                     const float** d_att);
+
+/*
+ * Decode a queue of n_jobs batches on n_slots handles (n_slots batches in flight).  Whenever a
+ * handle is free the next job is taken: job_fn(user, job, slot, h, CTCBS_JOB_LOAD) must make
+ * h ready for it (ctcbs_reset with that batch's posteriors); the batch is then stepped, with
+ * att_fn called with index = job, until it reports CTCBS_DONE, and
+ * job_fn(..., CTCBS_JOB_DONE) collects its result (ctcbs_finalize).  n_threads host threads
+ * (the caller's included) share the slots; the callbacks run on those threads, concurrently
+ * for different slots.  All handles must accept every job (same configuration, t_max and
+ * n_utt large enough).  Returns the first error (callbacks return 0 or a negative code).
+ */
+enum { CTCBS_JOB_LOAD = 0, CTCBS_JOB_DONE = 1 };
+typedef int (*ctcbs_job_fn)(void* user, int32_t job, int32_t slot, ctcbs_t* h, int32_t phase);
+int ctcbs_run_queue(ctcbs_t* const* hs, int32_t n_slots, int32_t n_jobs, ctcbs_job_fn job_fn,
+                    ctcbs_att_fn att_fn, void* user, int32_t n_threads);
+
 void ctcbs_destroy(ctcbs_t* h);
 
 const char* ctcbs_strerror(int code);

@@ -26,7 +26,8 @@ HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
 
 EXPORTS = ["ctcbs_create", "ctcbs_step", "ctcbs_poll", "ctcbs_finalize", "ctcbs_stats", "ctcbs_peek",
            "ctcbs_destroy", "ctcbs_strerror", "ctcbs_last_hip_error", "ctcbs_profile",
-           "ctcbs_profile_read", "ctcbs_reset"]
+           "ctcbs_profile_read", "ctcbs_reset", "ctcbs_hard_segments", "ctcbs_merge_pieces",
+           "ctcbs_plan_batches", "ctcbs_run_many", "ctcbs_att_replay", "ctcbs_run_queue"]
 
 
 def build():
@@ -90,6 +91,19 @@ def lib():
         L.ctcbs_strerror.restype = ctypes.c_char_p
         L.ctcbs_strerror.argtypes = [i32]
         L.ctcbs_last_hip_error.restype = i32
+        i64 = ctypes.c_int64
+        L.ctcbs_hard_segments.restype = i32
+        L.ctcbs_hard_segments.argtypes = [i64, i32, i32, vp, i32, ctypes.POINTER(i32)]
+        L.ctcbs_merge_pieces.restype = i32
+        L.ctcbs_merge_pieces.argtypes = [vp, i32, i32, i32, vp, i32, ctypes.POINTER(i32)]
+        L.ctcbs_plan_batches.restype = i32
+        L.ctcbs_plan_batches.argtypes = [vp, i32, i32, i64, vp, vp, i32, ctypes.POINTER(i32)]
+        L.ctcbs_run_many.restype = i32
+        L.ctcbs_run_many.argtypes = [vp, i32, vp, vp, i32]
+        L.ctcbs_run_queue.restype = i32
+        L.ctcbs_run_queue.argtypes = [vp, i32, i32, vp, vp, vp, i32]
+        L.ctcbs_att_replay.restype = i32
+        L.ctcbs_att_replay.argtypes = [vp, i32, i32, vp, vp]
         _lib = L
     return _lib
 
@@ -220,6 +234,135 @@ def ctcbs_peek(handle, what):
     if rc != OK:
         raise CtcbsError(rc)
     return out
+
+
+def _lengths_call(fn, *args):
+    """Two calls: the first sizes the output, the second fills it."""
+    n = ctypes.c_int32()
+    rc = fn(*args, None, 0, ctypes.byref(n))
+    if rc not in (OK, ECAP):
+        raise CtcbsError(rc)
+    out = np.empty(max(n.value, 1), dtype=np.int32)
+    if n.value:
+        rc = fn(*args, out.ctypes.data_as(ctypes.c_void_p), n.value, ctypes.byref(n))
+        if rc != OK:
+            raise CtcbsError(rc)
+    return out[:n.value].copy()
+
+
+def ctcbs_hard_segments(n_frames, min_len, max_len):
+    """-> int32 lengths of the hard segmentation of a recording of n_frames frames."""
+    return _lengths_call(lib().ctcbs_hard_segments, int(n_frames), int(min_len), int(max_len))
+
+
+def ctcbs_merge_pieces(piece_len, min_len, max_len):
+    """-> int32 segment lengths from voice-activity piece lengths."""
+    pl = np.ascontiguousarray(piece_len, dtype=np.int32)
+    return _lengths_call(lib().ctcbs_merge_pieces, pl.ctypes.data_as(ctypes.c_void_p), pl.size, int(min_len),
+                         int(max_len))
+
+
+def ctcbs_plan_batches(lens, max_utt, max_padded_frames=0):
+    """-> (order, begin): batch b holds segments order[begin[b]:begin[b+1]], longest first."""
+    ln = np.ascontiguousarray(lens, dtype=np.int32)
+    order = np.empty(max(ln.size, 1), dtype=np.int32)
+    nb = ctypes.c_int32()
+    vp = ctypes.c_void_p
+    rc = lib().ctcbs_plan_batches(ln.ctypes.data_as(vp), ln.size, int(max_utt), int(max_padded_frames),
+                                  order.ctypes.data_as(vp), None, 0, ctypes.byref(nb))
+    if rc not in (OK, ECAP):
+        raise CtcbsError(rc)
+    begin = np.empty(nb.value + 1, dtype=np.int32)
+    rc = lib().ctcbs_plan_batches(ln.ctypes.data_as(vp), ln.size, int(max_utt), int(max_padded_frames),
+                                  order.ctypes.data_as(vp), begin.ctypes.data_as(vp), nb.value, ctypes.byref(nb))
+    if rc != OK:
+        raise CtcbsError(rc)
+    return order[:ln.size].copy(), begin
+
+
+class Replay(ctypes.Structure):
+    """Mirror of ctcbs_replay_t."""
+    _fields_ = [("d_att", ctypes.POINTER(ctypes.c_void_p)), ("n_steps", ctypes.c_int32)]
+
+
+ATT_FN = ctypes.CFUNCTYPE(ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
+                          ctypes.POINTER(StepOut), ctypes.POINTER(ctypes.c_void_p))
+
+
+def ctcbs_run_many(handles, att_fn=None, replay=None, n_threads=1):
+    """Decode the batches of `handles` at once.  Either `replay`: per handle a list of device
+    pointers (ints), one [U][Wb][V] row block per step, served by the library's own
+    ctcbs_att_replay; or `att_fn(index, step, prev_out_or_None) -> device pointer` (a Python
+    callable; use one thread with it)."""
+    L = lib()
+    hs = (ctypes.c_void_p * len(handles))(*handles)
+    if replay is not None:
+        keep = [(ctypes.c_void_p * len(r))(*r) for r in replay]
+        tabs = (Replay * len(handles))()
+        for i, k in enumerate(keep):
+            tabs[i].d_att = ctypes.cast(k, ctypes.POINTER(ctypes.c_void_p))
+            tabs[i].n_steps = len(replay[i])
+        fn = ctypes.cast(L.ctcbs_att_replay, ctypes.c_void_p)
+        rc = L.ctcbs_run_many(hs, len(handles), fn, ctypes.cast(tabs, ctypes.c_void_p), int(n_threads))
+    else:
+        def tramp(_user, index, step, prev, d_att):
+            try:
+                d_att[0] = _ptr(att_fn(index, step, prev.contents if prev else None))
+                return OK
+            except Exception:                       # never let an exception cross the C frames
+                return EINVAL
+        cb = ATT_FN(tramp)
+        rc = L.ctcbs_run_many(hs, len(handles), ctypes.cast(cb, ctypes.c_void_p), None, int(n_threads))
+    if rc != OK:
+        raise CtcbsError(rc)
+
+
+JOB_LOAD, JOB_DONE = 0, 1
+JOB_FN = ctypes.CFUNCTYPE(ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
+                          ctypes.c_int32)
+
+
+def ctcbs_run_queue(handles, n_jobs, job_fn, replay=None, att_fn=None, n_threads=1):
+    """Decode n_jobs batches on the given handles (as many in flight).  job_fn(job, slot, handle,
+    phase): phase JOB_LOAD -> ctcbs_reset(handle, ...) for that batch, JOB_DONE -> ctcbs_finalize.
+    Attention rows: `replay` (per job a list of device pointers, one per step) or a Python
+    `att_fn(job, step, prev)` (then use one thread).  Callbacks run on the executor's threads."""
+    L = lib()
+    hs = (ctypes.c_void_p * len(handles))(*handles)
+    errors = []
+
+    def job_tramp(_user, job, slot, h, phase):
+        try:
+            job_fn(job, slot, h, phase)
+            return OK
+        except Exception as e:                      # never let an exception cross the C frames
+            errors.append(e)
+            return EINVAL
+    jcb = JOB_FN(job_tramp)
+    if replay is not None:
+        keep = [(ctypes.c_void_p * len(r))(*r) for r in replay]
+        tabs = (Replay * n_jobs)()
+        for i, k in enumerate(keep):
+            tabs[i].d_att = ctypes.cast(k, ctypes.POINTER(ctypes.c_void_p))
+            tabs[i].n_steps = len(replay[i])
+        rc = L.ctcbs_run_queue(hs, len(handles), n_jobs, ctypes.cast(jcb, ctypes.c_void_p),
+                               ctypes.cast(L.ctcbs_att_replay, ctypes.c_void_p),
+                               ctypes.cast(tabs, ctypes.c_void_p), int(n_threads))
+    else:
+        def tramp(_user, index, step, prev, d_att):
+            try:
+                d_att[0] = _ptr(att_fn(index, step, prev.contents if prev else None))
+                return OK
+            except Exception as e:
+                errors.append(e)
+                return EINVAL
+        cb = ATT_FN(tramp)
+        rc = L.ctcbs_run_queue(hs, len(handles), n_jobs, ctypes.cast(jcb, ctypes.c_void_p),
+                               ctypes.cast(cb, ctypes.c_void_p), None, int(n_threads))
+    if errors:
+        raise errors[0]
+    if rc != OK:
+        raise CtcbsError(rc)
 
 
 def ctcbs_destroy(handle):

@@ -20,15 +20,23 @@
 #define MAX_EOS_RUN 32
 
 // Phase time stamps for kernel tuning; compiled in only with -DCTCBS_TRACE (never in the
-// shipped library).
+// shipped library).  TRACE_POINT stores at once (cheap to place, but the store is then waited
+// for by the next wait on the memory counter); TRACE_MARK keeps the stamp in registers and
+// TRACE_FLUSH stores them all at the end of the kernel, which leaves the timing undisturbed.
 #ifdef CTCBS_TRACE
 #define TRACE_POINT(p, blk, i) do { if ((p).trace && threadIdx.x == 0) (p).trace[(size_t)(blk) * 16 + (i)] = wall_clock64(); } while (0)
-#define TRACE_RAW(ptr, i) do { if ((ptr) && threadIdx.x == 0) (ptr)[i] = wall_clock64(); } while (0)
-#define TRACE_POINT_T(p, blk, i, thr) do { if ((p).trace && threadIdx.x == (thr)) (p).trace[(size_t)(blk) * 16 + (i)] = wall_clock64(); } while (0)
+#define TRACE_DECL unsigned long long tr_[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}
+#define TRACE_MARK(i) do { tr_[i] = wall_clock64(); } while (0)
+#define TRACE_MARK_AT(ptr, i) do { (ptr)[i] = wall_clock64(); } while (0)
+#define TRACE_ARG tr_
+#define TRACE_FLUSH(p, blk) do { if ((p).trace && threadIdx.x == 0) { _Pragma("unroll") for (int i_ = 0; i_ < 16; ++i_) if (tr_[i_]) (p).trace[(size_t)(blk) * 16 + i_] = tr_[i_]; } } while (0)
 #else
 #define TRACE_POINT(p, blk, i) do { } while (0)
-#define TRACE_RAW(ptr, i) do { } while (0)
-#define TRACE_POINT_T(p, blk, i, thr) do { } while (0)
+#define TRACE_DECL do { } while (0)
+#define TRACE_MARK(i) do { } while (0)
+#define TRACE_MARK_AT(ptr, i) do { } while (0)
+#define TRACE_ARG nullptr
+#define TRACE_FLUSH(p, blk) do { } while (0)
 #endif
 
 struct UttState {            // per utterance, touched by one thread of the select kernel

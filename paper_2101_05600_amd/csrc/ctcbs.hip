@@ -28,6 +28,7 @@ struct ctcbs {
   Params p;
   ScoreSmem sm;
   hipStream_t stream;
+  int device;          // the device the handle lives on (current at creation)
   std::vector<void*> allocs;
   std::vector<int32_t> lens, lmax;
   int32_t step;        // steps enqueued
@@ -262,6 +263,7 @@ extern "C" int ctcbs_create(const ctcbs_config_t* cfg, const float* d_ctc_logp, 
   h->h_flag = nullptr; h->throttle_made = false;
   h->cfg = *cfg;
   h->stream = (hipStream_t)cfg->stream;
+  if (hipGetDevice(&h->device) != hipSuccess) { g_last_hip = (int)hipGetLastError(); delete h; return CTCBS_EHIP; }
   rc = create_impl(h, d_ctc_logp, h_lens);
   if (rc != CTCBS_OK) { free_all(h); delete h; return rc; }
   *out = h;
@@ -465,6 +467,8 @@ extern "C" int ctcbs_trace_read(ctcbs_t* h, unsigned long long* dst) {
   return CTCBS_OK;
 }
 #endif
+
+#include "sched.h"
 
 extern "C" void ctcbs_destroy(ctcbs_t* h) {
   if (!h) return;

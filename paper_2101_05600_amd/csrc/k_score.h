@@ -57,7 +57,7 @@ __device__ __forceinline__ bool select_pivot(const float4 (&v)[PIVOT_NV4], int K
   for (int k = 0; k < PIVOT_NV4; ++k)
     fmx = fmaxf(fmx, fmaxf(fmaxf(v[k].x, v[k].y), fmaxf(v[k].z, v[k].w)));
   const uint32_t lmax = att_key(fmx, -1, -2, -2);
-  TRACE_RAW(tr, 6);
+  TRACE_MARK_AT(tr, 6);
   // r-th largest lane maximum of this wave, by bisection on the upper 16 key bits (sign,
   // exponent, 7 mantissa bits): stopping early only lowers the pivot, which stays valid
   const int r = (K + NW - 1) / NW;
@@ -67,7 +67,7 @@ __device__ __forceinline__ bool select_pivot(const float4 (&v)[PIVOT_NV4], int K
     const uint32_t trial = thr | (1u << bit);
     if (__popcll(__ballot(lmax >= trial)) >= r) thr = trial;
   }
-  TRACE_RAW(tr, 7);
+  TRACE_MARK_AT(tr, 7);
   if (lane == 0) s_w[w] = thr;
   lds_barrier();
   uint32_t Lk = s_w[0];
@@ -91,7 +91,7 @@ __device__ __forceinline__ bool select_pivot(const float4 (&v)[PIVOT_NV4], int K
 #pragma unroll
   for (int i = 0; i < NW; ++i) { const int c = (int)s_w[NW + i]; base += i < w ? c : 0; total += c; }
   if (total > PIVOT_CAP || total < K) return false;
-  TRACE_RAW(tr, 14);
+  TRACE_MARK_AT(tr, 14);
   const bool linf = (L == ninf);                           // then excluded ids (held as -inf) are hits too
   int pos = base + inc - cnt;
   // per float4 slot, one hit per trip (most lanes have none, hardly any more than one)
@@ -113,7 +113,7 @@ __device__ __forceinline__ bool select_pivot(const float4 (&v)[PIVOT_NV4], int K
   const int n4 = (n + 3) >> 2;
   if (tid < 4 && n + tid < 4 * n4) s_ent[n + tid] = 0ull;    // pad to a multiple of four
   lds_barrier();
-  TRACE_RAW(tr, 15);
+  TRACE_MARK_AT(tr, 15);
   // exact rank: four lanes per entry, each comparing against a quarter of the list (two entries
   // per read), partial ranks summed inside the quad; the rank is the output slot
   const int part = tid & 3;
@@ -280,6 +280,7 @@ __global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, cons
 
   const int tid = threadIdx.x;
   const int grp = blockIdx.x;
+  TRACE_DECL;
   const int u = grp / p.Wb;
   const int K = p.K, V = p.V;
   const bool smallk = (K <= BLOCK);
@@ -324,7 +325,7 @@ __global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, cons
     return;
   }
 
-  TRACE_POINT(p, grp, 0);
+  TRACE_MARK(0);
   uint32_t* s_work = (uint32_t*)(smem + sm.off_work);
   float* s_F = (float*)(smem + sm.off_f);
   float* s_Fb = s_F + sm.wp_max;
@@ -387,7 +388,7 @@ __global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, cons
     eos_a = arow[p.eos_id];               // (logits mode: shifted by the row's log-sum-exp below)
   }
 
-  TRACE_POINT(p, grp, 1);
+  TRACE_MARK(1);
   // ---------------- stage the f terms of the window in LDS ---------------------------------
   for (int i = tid; i < Wp; i += BLOCK) {
     const int t = t0 + i;
@@ -401,7 +402,7 @@ __global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, cons
   const int R = p.eos_run;
   const bool e2 = (p.end_flags & 4) && R > 0 && T >= R && W > 0 && e == T && re == T &&
                   max(s, rs) <= T - R + 1;
-  TRACE_POINT(p, grp, 2);
+  TRACE_MARK(2);
 
   // ---------------- 1. candidates -----------------------------------------------------------
   if (p.restricted) {
@@ -424,7 +425,7 @@ __global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, cons
         }
       }
       ok = select_pivot<BLOCK>(arow_r, K, p.blank_id, p.eos_id, (unsigned long long*)s_work,
-                               s_w, smallk, s_cid, s_av, g_cid, p.trace ? p.trace + (size_t)grp * 16 : nullptr);
+                               s_w, smallk, s_cid, s_av, g_cid, TRACE_ARG);
     }
     if (!ok) select_radix<BLOCK>(arow, V, K, p.blank_id, p.eos_id, s_work, s_scan, s_sel, smallk, s_cid, s_av, g_cid);
   } else {
@@ -437,7 +438,7 @@ __global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, cons
   }
   // candidates and f terms visible to the whole block (large K: the ids are read back from global memory)
   if (smallk) lds_barrier(); else __syncthreads();
-  TRACE_POINT(p, grp, 3);
+  TRACE_MARK(3);
 
   // ---------------- 3. prefix scores ----------------------------------------------------
   constexpr int NSG = BLOCK / LPC;
@@ -506,7 +507,7 @@ __global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, cons
     }
   }
 
-  TRACE_POINT(p, grp, 4);
+  TRACE_MARK(4);
   // ---------------- 4. eos, eos-run rule, group list -------------------------------------
   if (tid == 0) {
     const float ce = (rs <= T && re >= T) ? canon0(lae(eos_n, eos_b)) : LOG0F;
@@ -628,7 +629,8 @@ __global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, cons
       g_joint[c] = s_Jraw[c];
     }
   }
-  TRACE_POINT(p, grp, 5);
+  TRACE_MARK(5);
+  TRACE_FLUSH(p, grp);
 }
 
 // Group list for large candidate sets (K > block size): Wb rounds of a block-wide argmax

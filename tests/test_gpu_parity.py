@@ -389,3 +389,64 @@ def test_batch_union_window(m1, m2):
     w2 = dict(w); w2["win_union"] = 0
     rep2, res2 = lockstep_decode(w2, ctc, lens)
     assert res["cells"] / res["steps"] >= res2["cells"] / res2["steps"] * 0.999
+
+
+def test_run_many_reproduces_single_decodes():
+    """The library's executor (several batches in flight, two host threads, recorded rows served by
+    ctcbs_att_replay) returns for every batch exactly what a lone decode of that batch returns;
+    the lone decodes themselves are validated against the oracle step by step."""
+    import torch
+    import paper_2101_05600_amd as m
+    ws = [small("cfg1", n_utt=3, t_lo=40, t_hi=110, vocab=600, beam=4, cand_k=16, win_m1=15, win_m2=15,
+                end_flags=7, eos_run=5, seed=2101 + i) for i in range(3)]
+    singles, recs, decs = [], [], []
+    inputs = [make_inputs(w) for w in ws]
+    T = max(ctc.shape[1] for _, ctc in inputs)             # one frame pitch for all: any handle takes any batch
+
+    def padded(ctc):
+        out = np.full((ctc.shape[0], T, ctc.shape[2]), np.nan, np.float32)
+        out[:, :ctc.shape[1]] = ctc
+        return out
+    inputs = [(lens, padded(ctc)) for lens, ctc in inputs]
+    try:
+        for w, (lens, ctc) in zip(ws, inputs):
+            rows = []
+            rep, res = lockstep_decode(w, ctc, lens, gpu_att_fn=lambda a, rows=rows: rows.append(a.copy()) or a)
+            assert rep["max_score_err"] < 1e-4
+            singles.append(res)
+            recs.append(rows)
+            decs.append(GpuDecoder(dict(w, stream=torch.cuda.Stream().cuda_stream), ctc, lens, poll_every=4))
+        keep = [[torch.from_numpy(r).cuda() for r in rows] for rows in recs]   # dead rows hold NaN
+        torch.cuda.synchronize()
+        m.ctcbs_run_many([d.h for d in decs], replay=[[t.data_ptr() for t in k] for k in keep], n_threads=2)
+        for d, res in zip(decs, singles):
+            tok, nt, sc, frm, fl = d.finalize()
+            assert np.array_equal(tok, res["tokens"]) and np.array_equal(nt, res["ntok"])
+            assert np.array_equal(sc, res["score"]) and np.array_equal(fl, res["flags"])
+        # a Python provider (one thread): same results once more on fresh state
+        for d, (lens, ctc) in zip(decs, inputs):
+            m.ctcbs_reset(d.h, torch.from_numpy(ctc).cuda(), lens)
+        m.ctcbs_run_many([d.h for d in decs], att_fn=lambda i, step, prev: keep[i][min(step, len(keep[i])) - 1])
+        for d, res in zip(decs, singles):
+            tok, nt, sc, frm, fl = d.finalize()
+            assert np.array_equal(tok, res["tokens"]) and np.array_equal(sc, res["score"])
+        # the job queue: five jobs (the three batches, two of them twice) on two of the handles
+        jobs = [0, 1, 2, 1, 0]
+        data = [(torch.from_numpy(ctc).cuda(), lens) for lens, ctc in inputs]
+        got = [None] * len(jobs)
+
+        def job_fn(job, slot, h, phase):
+            b = jobs[job]
+            if phase == m.JOB_LOAD:
+                m.ctcbs_reset(h, data[b][0], data[b][1])
+            else:
+                got[job] = m.ctcbs_finalize(h, 3, singles[b]["tokens"].shape[1])
+        # (the three batches share shapes: any handle takes any of them after a reset)
+        m.ctcbs_run_queue([decs[0].h, decs[1].h], len(jobs), job_fn,
+                          replay=[[t.data_ptr() for t in keep[b]] for b in jobs], n_threads=2)
+        for job, b in enumerate(jobs):
+            tok, nt, sc, frm, fl = got[job]
+            assert np.array_equal(tok, singles[b]["tokens"]) and np.array_equal(sc, singles[b]["score"])
+    finally:
+        for d in decs:
+            d.close()
