@@ -285,29 +285,30 @@ __global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, cons
   const int K = p.K, V = p.V;
   const bool smallk = (K <= BLOCK);
 
-  // ---------------- first round of loads: the attention row and g's record -------------------
-  // Both are issued before the liveness test so that the row is already on its way while the
-  // record arrives (the step input holds a row for every slot, live or not; a dead slot's row
-  // is loaded and ignored).
-  const float* arow = att + (size_t)grp * V;
-  // attention row -> registers (restricted mode, rows that fit): PIVOT_NV4 float4 per lane, all
-  // in flight together (clamped, unconditional)
-  const bool in_regs = p.restricted && (V & 3) == 0 && (V >> 2) <= PIVOT_NV4 * BLOCK;
-  float4 arow_r[PIVOT_NV4];
-  if (in_regs) {
-    const float4* a4 = (const float4*)arow;
-    const int nv4 = V >> 2;
-#pragma unroll
-    for (int k = 0; k < PIVOT_NV4; ++k) arow_r[k] = a4[min(tid + k * BLOCK, nv4 - 1)];
-  }
+  // ---------------- first round of loads: g's record, then its attention row ----------------
+  // The record comes through the scalar path (uniform addresses, nothing in this kernel writes
+  // them before): it is back in a fraction of a vector load's latency and is not ordered behind
+  // the row loads issued next.  A dead slot's row is never read: half of the groups of a
+  // typical batch are dead on average (utterances finish at different steps).
   // (the utterance's finished byte is fetched as part of its aligned word: a uniform word load
-  // can go through the scalar path, which is not ordered behind the row loads)
+  // can take the scalar path, a byte load cannot)
   const uint32_t fin_word = ((const uint32_t*)p.finished)[u >> 2];
   const int dead = (int)((fin_word >> (8 * (u & 3))) & 0xffu) | (p.h_live[cur][grp] == 0);
   const int T = p.lens[u];
   const int tau = p.h_tau[cur][grp], tau_end = p.h_tau_end[cur][grp];
   const int rs = p.h_rs[cur][grp], re = p.h_re[cur][grp], last = p.h_last[cur][grp];
   const double off = p.h_off[cur][grp], acum = p.h_att[cur][grp];
+  const float* arow = att + (size_t)grp * V;
+  // attention row -> registers (restricted mode, rows that fit): PIVOT_NV4 float4 per lane, all
+  // in flight together (clamped, unconditional for a live slot)
+  const bool in_regs = p.restricted && (V & 3) == 0 && (V >> 2) <= PIVOT_NV4 * BLOCK;
+  float4 arow_r[PIVOT_NV4];
+  if (in_regs && !dead) {
+    const float4* a4 = (const float4*)arow;
+    const int nv4 = V >> 2;
+#pragma unroll
+    for (int k = 0; k < PIVOT_NV4; ++k) arow_r[k] = a4[min(tid + k * BLOCK, nv4 - 1)];
+  }
   // publish the count of finished utterances (as of the previous step) where the host can
   // read it without synchronising: one writer, plain store to device-mapped pinned memory
   if (grp == 0 && tid == 0) {
