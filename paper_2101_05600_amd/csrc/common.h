@@ -15,6 +15,9 @@
 #define LOG0F (-1.0e30f)
 #define LOG0_CLASS (-1.0e29f)
 #define LOG0D (-1.0e30)
+// Blank log-posteriors enter the per-frame reference B_t (see Params::Bcum) floored at this value, so
+// that B_t stays finite even if a frame gives blank probability zero.
+#define BLANK_FLOOR (-1.0e4f)
 #define MAX_BEAM 32
 #define MAX_END_M 8
 #define MAX_EOS_RUN 32
@@ -62,7 +65,13 @@ struct Params {
   float* xT;
   const int32_t* lens;       // [U]
   const int32_t* lmax;       // [U] step cap per utterance
-  // hypothesis state, two buffers (index b): forward variables [b][U][Wb][Tp] (relative) and
+  // Cumulative blank log-posterior per utterance, fp64: Bcum[u*Tp + t] = sum_{v<=t} max(x_v(blank),
+  // BLANK_FLOOR), Bcum[u*Tp] = 0.  Forward variables are stored with B_t taken out: for a hypothesis
+  // g with offset off'(g), gamma_t(g) = stored_t + B_t + off'(g).  On the path that stays in blank the
+  // stored value does not change from frame to frame, so stored values stay within tens of nats of
+  // zero however long the utterance is, and the large part (B_t) is carried in fp64.
+  double* Bcum;
+  // hypothesis state, two buffers (index b): forward variables [b][U][Wb][Tp] (stored form) and
   // per-hypothesis records [b][U][Wb]
   float* gn[2];
   float* gb[2];
@@ -72,7 +81,8 @@ struct Params {
   int32_t* h_re[2];
   int32_t* h_tau[2];
   int32_t* h_tau_end[2];
-  double* h_off[2];          // log psi(g): cumulative CTC prefix score
+  int32_t* h_ref[2];         // reference frame r: prefix-score increments are relative to off' + B_r
+  double* h_off[2];          // off'(g): log psi(g) = off'(g) + B_r(g) up to the rounding of the re-basing
   double* h_att[2];          // cumulative attention log-prob, Eq. (2)
   double* h_joint[2];        // joint score of the hypothesis
   // per-step scratch between the score and the select kernel

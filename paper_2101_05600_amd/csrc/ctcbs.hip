@@ -190,12 +190,13 @@ static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens)
   int32_t*& d_lens = h->d_lens; int32_t*& d_lmax = h->d_lmax;
 #define A(ptr, n) if ((rc = dev_alloc(h, &(ptr), (n))) != CTCBS_OK) return rc
   A(p.xT, (size_t)U * V * p.Tp);
+  A(p.Bcum, (size_t)U * p.Tp);
   A(d_lens, (size_t)U); A(d_lmax, (size_t)U);
   p.lens = d_lens; p.lmax = d_lmax;
   for (int b = 0; b < 2; ++b) {
     A(p.gn[b], UW * p.Tp); A(p.gb[b], UW * p.Tp);
     A(p.h_live[b], UW); A(p.h_last[b], UW); A(p.h_rs[b], UW); A(p.h_re[b], UW);
-    A(p.h_tau[b], UW); A(p.h_tau_end[b], UW);
+    A(p.h_tau[b], UW); A(p.h_tau_end[b], UW); A(p.h_ref[b], UW);
     A(p.h_off[b], UW); A(p.h_att[b], UW); A(p.h_joint[b], UW);
   }
   A(p.win_s, UW); A(p.win_e, UW);

@@ -33,34 +33,42 @@ __global__ __launch_bounds__(256) void k_transpose(Params p, const float* __rest
   }
 }
 
-// Empty-prefix state: z_0 = blank (first alignment rule of Sec. 2.1), so the blank
-// variable of the empty hypothesis at frame t is the running sum of the blank
-// log-posteriors and the label variable is log0.  One wave per utterance, fp64 running sum.
+// Per-frame reference and empty-prefix state.  z_0 = blank (first alignment rule of Sec. 2.1), so
+// the blank variable of the empty hypothesis at frame t is the running sum of the blank
+// log-posteriors and the label variable is log0.  That running sum (fp64, each term floored at
+// BLANK_FLOOR) is also the reference B_t every stored forward variable is taken relative to: the
+// empty hypothesis's stored blank variable is therefore 0 at every frame (minus whatever the
+// floor cut off: log0 from the first frame on whose blank probability is zero).
+// One wave per utterance.
 __global__ __launch_bounds__(64) void k_init_state(Params p) {
   const int u = blockIdx.x, lane = threadIdx.x;
   const int T = p.lens[u];
   const size_t hyp0 = (size_t)u * p.Wb;
   float* gn = p.gn[0] + hyp0 * p.Tp;
   float* gb = p.gb[0] + hyp0 * p.Tp;
+  double* Bu = p.Bcum + (size_t)u * p.Tp;
   const float* xb = p.xT + ((size_t)u * p.V + p.blank_id) * p.Tp;
-  double carry = 0.0;
-  if (lane == 0) { gn[0] = LOG0F; gb[0] = 0.0f; }
+  double carry = 0.0, carry_cut = 0.0;
+  if (lane == 0) { gn[0] = LOG0F; gb[0] = 0.0f; Bu[0] = 0.0; }
   for (int base = 1; base <= T; base += 64) {
     int t = base + lane;
-    double v = (t <= T) ? (double)xb[t] : 0.0;
+    const float x0 = (t <= T) ? xb[t] : 0.0f;
+    double v = (double)fmaxf(x0, BLANK_FLOOR);           // floored term of B_t
+    double c = (double)x0 - v;                            // what the floor cut off (0 or negative)
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
-      double n = __shfl_up(v, o);
-      if (lane >= o) v += n;
+      double n = __shfl_up(v, o), nc = __shfl_up(c, o);
+      if (lane >= o) { v += n; c += nc; }
     }
-    v += carry;
-    if (t <= T) { gb[t] = fmaxf((float)v, LOG0F); gn[t] = LOG0F; }
-    carry = __shfl(v, 63);
+    v += carry; c += carry_cut;
+    if (t <= T) { Bu[t] = v; gb[t] = fmaxf((float)c, LOG0F); gn[t] = LOG0F; }
+    carry = __shfl(v, 63); carry_cut = __shfl(c, 63);
   }
+  for (int t = T + 1 + lane; t < p.Tp; t += 64) Bu[t] = carry;   // (never weighted: keeps reads defined)
   for (int j = lane; j < p.Wb; j += 64) {
     size_t h = hyp0 + j;
     p.h_live[0][h] = (j == 0); p.h_last[0][h] = -1;
-    p.h_rs[0][h] = 0; p.h_re[0][h] = T; p.h_tau[0][h] = 0; p.h_tau_end[0][h] = 0;
+    p.h_rs[0][h] = 0; p.h_re[0][h] = T; p.h_tau[0][h] = 0; p.h_tau_end[0][h] = 0; p.h_ref[0][h] = 0;
     p.h_off[0][h] = 0.0; p.h_att[0][h] = 0.0; p.h_joint[0][h] = 0.0;
     p.h_live[1][h] = 0;
     p.out_live[h] = (j == 0); p.out_parent[h] = 0; p.out_token[h] = -1; p.out_score[h] = 0.0f;

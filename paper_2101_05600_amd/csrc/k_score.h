@@ -297,6 +297,7 @@ __global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, cons
   const int T = p.lens[u];
   const int tau = p.h_tau[cur][grp], tau_end = p.h_tau_end[cur][grp];
   const int rs = p.h_rs[cur][grp], re = p.h_re[cur][grp], last = p.h_last[cur][grp];
+  const int ref = p.h_ref[cur][grp];
   const double off = p.h_off[cur][grp], acum = p.h_att[cur][grp];
   const float* arow = att + (size_t)grp * V;
   // attention row -> registers (restricted mode, rows that fit): PIVOT_NV4 float4 per lane, all
@@ -381,9 +382,15 @@ __global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, cons
   const int Wp = n4 * 4;
   const float* gn = p.gn[cur] + (size_t)grp * p.Tp;
   const float* gb = p.gb[cur] + (size_t)grp * p.Tp;
+  // Stored forward variables have the per-frame reference B_t taken out (see Params::Bcum); all
+  // increments of this step are relative to off'(g) + B_r, r = g's reference frame
+  const double* Bu = p.Bcum + (size_t)u * p.Tp;
+  const double Bref = Bu[ref];
+  const double offr = off + Bref;
 
   // eos inputs (thread 0), fetched now so that the epilogue does not wait for them
   float eos_n = LOG0F, eos_b = LOG0F, eos_a = 0.0f;
+  const double BT = Bu[T] - Bref;                          // B_T - B_r
   if (tid == 0) {
     if (rs <= T && re >= T) { eos_n = gn[T]; eos_b = gb[T]; }
     eos_a = arow[p.eos_id];               // (logits mode: shifted by the row's log-sum-exp below)
@@ -396,7 +403,12 @@ __global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, cons
     float f = LOG0F, fb = LOG0F;
     if (t >= s && t <= e) {
       const int pr = t - 1;
-      if (pr >= rs && pr <= re) { const float n = gn[pr]; fb = gb[pr]; f = lae(n, fb); }
+      if (pr >= rs && pr <= re) {
+        // gamma_{t-1}(g) - off' - B_r = stored_{t-1} + (B_{t-1} - B_r); far from r the second part is
+        // large and coarse in fp32, and the term is then negligible by that same factor
+        const float bt = (float)(Bu[pr] - Bref);
+        const float n = gn[pr]; fb = gb[pr]; f = canon0(lae(n, fb) + bt); fb = canon0(fb + bt);
+      }
     }
     s_F[i] = f; s_Fb[i] = fb;
   }
@@ -497,7 +509,7 @@ __global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, cons
       if (q == 0) {
         const float av = (smallk ? s_av[c] : arow[id]) - row_lse;
         const bool valid = inc > LOG0_CLASS;
-        const double ctc = valid ? off + (double)inc : LOG0D;
+        const double ctc = valid ? offr + (double)inc : LOG0D;
         const double J = valid ? lam * ctc + (1.0 - lam) * (double)av + jbase : LOG0D;
         // small K: scores stay in LDS for the ranking below, the per-candidate arrays in global memory
         // (read back by ctcbs_peek only) are written from there at the very end, so that no store
@@ -513,7 +525,7 @@ __global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, cons
   if (tid == 0) {
     const float ce = (rs <= T && re >= T) ? canon0(lae(eos_n, eos_b)) : LOG0F;
     const bool v = ce > LOG0_CLASS;
-    const double ctc = v ? off + (double)ce : LOG0D;
+    const double ctc = v ? offr + BT + (double)ce : LOG0D;  // phi_T(g) = off' + B_T + stored
     p.ctc_eos[grp] = ctc;
     p.joint_eos[grp] = v ? lam * ctc + (1.0 - lam) * (double)(eos_a - row_lse) + jbase : LOG0D;
     p.win_s[grp] = s; p.win_e[grp] = e;
@@ -529,7 +541,7 @@ __global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, cons
     xt = row16_max(xt);
     xt = fmaxf(fmaxf(lane_f(xt, 0), lane_f(xt, 16)), fmaxf(lane_f(xt, 32), lane_f(xt, 48)));
     if ((tid & 63) == 0) s_e2w[tid >> 6] = xt;
-    if (tid == 0) s_e2w[BLOCK / 64] = (rs <= T && re >= T) ? canon0(lae(eos_n, eos_b)) : LOG0F;
+    if (tid == 0) s_e2w[BLOCK / 64] = (rs <= T && re >= T) ? canon0(lae(eos_n, eos_b) + (float)BT) : LOG0F;
     lds_barrier();
     float XT = s_e2w[0];
 #pragma unroll
@@ -577,7 +589,7 @@ __global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, cons
     lds_barrier();
     if (tid < R) {
       const int t = T - R + 1 + tid;
-      const float Et = canon0(lae(gn[t], gb[t]));
+      const float Et = canon0(lae(gn[t], gb[t]) + (float)(Bu[t] - Bref));
       float X = s_e2w[tid];
 #pragma unroll
       for (int w2 = 1; w2 < BLOCK / 64; ++w2) X = fmaxf(X, s_e2w[w2 * MAX_EOS_RUN + tid]);
@@ -626,7 +638,7 @@ __global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, cons
     for (int c = tid; c < K; c += BLOCK) {
       const float inc = s_inc[c];
       g_cid[c] = s_cid[c]; g_inc[c] = inc; g_catt[c] = s_av[c];
-      g_ctc[c] = inc > LOG0_CLASS ? off + (double)inc : LOG0D;
+      g_ctc[c] = inc > LOG0_CLASS ? offr + (double)inc : LOG0D;
       g_joint[c] = s_Jraw[c];
     }
   }

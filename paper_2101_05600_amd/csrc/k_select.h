@@ -62,27 +62,37 @@ __device__ __forceinline__ ArgMax wave_argmax(ArgMax x) {
 // Forward variables of one new hypothesis (parent slot `par` extended by `tok`) over the
 // parent's window, by one wave: two scans of affine maps in the (logaddexp, +) semiring, 128
 // frames per pass (each lane owns two consecutive frames, composes their two maps, the wave
-// scans the composed maps, and the lane then replays its own two frames).  Writes the new
-// state (re-based on the child's own prefix score) into slot n of the other buffer and returns
-// tau / tau~ (first argmax from the parent's tau on; the parent's values if nothing is finite).
+// scans the composed maps, and the lane then replays its own two frames).
+// The recurrence runs on the stored form of the variables (per-frame reference B_t taken out,
+// see Params::Bcum): with x'_t(c) = x_t(c) - max(x_t(blank), floor) and d_t = x_t(blank) -
+// max(x_t(blank), floor) (zero unless the floor cut),
+//   n_t = (n_{t-1} (+) f_t) + x'_t(c),     b_t = (n_{t-1} (+) b_{t-1}) + d_t,
+// so that staying in blank costs nothing and values do not drift with t.  The child's state is
+// re-based by delta = inc + (B_r - B_r'), r the parent's reference frame and r' = the parent's
+// tau the child's: its values are then near zero around its own tau.  Writes the new state into
+// slot n of the other buffer and returns delta and tau / tau~ (first argmax of the true variables,
+// stored + B_t, from the parent's tau on; the parent's values if nothing is finite).
 struct SurvivorIn {
-  int par, tok, s, en, rs, re, ptau, ptau_end, plast;
+  int par, tok, s, en, rs, re, ptau, ptau_end, plast, pref;
   float inc;
 };
 __device__ __forceinline__ void wave_survivor(const Params& p, int u, int n, int cur, const SurvivorIn& in,
-                                              int& arg_n, int& arg_b) {
+                                              int& arg_n, int& arg_b, float& delta_out) {
   const int lane = threadIdx.x & 63;
   const size_t h0 = (size_t)u * p.Wb;
   const size_t hp = h0 + in.par;
   const float* xu = p.xT + (size_t)u * p.V * p.Tp;
   const float* x0 = xu + (size_t)p.blank_id * p.Tp;
   const float* xc = xu + (size_t)in.tok * p.Tp;
+  const double* Bu = p.Bcum + (size_t)u * p.Tp;
   const float* pgn = p.gn[cur] + hp * p.Tp;
   const float* pgb = p.gb[cur] + hp * p.Tp;
   float* cgn = p.gn[cur ^ 1] + (h0 + n) * p.Tp;
   float* cgb = p.gb[cur ^ 1] + (h0 + n) * p.Tp;
   const int s = in.s, en = in.en, rs = in.rs, re = in.re;
-  const float inc = in.inc;
+  const double Bnew = Bu[in.ptau];                       // the child's reference frame is the parent's tau
+  const float delta = in.inc + (float)(Bu[in.pref] - Bnew);
+  delta_out = delta;
   const bool rep = (in.tok == in.plast);
   const int lo = max(s, in.ptau);
   float carry_n = LOG0F, carry_b = LOG0F;
@@ -94,11 +104,14 @@ __device__ __forceinline__ void wave_survivor(const Params& p, int u, int n, int
     const int tac = min(ta, en), tbc = min(tb, en);      // clamped: loads are unconditional
     const float gna = pgn[max(tac - 1, 0)], gba = pgb[max(tac - 1, 0)];
     const float gnb = pgn[tbc - 1], gbb = pgb[tbc - 1];
-    const float xa = xc[tac], xb = xc[tbc], x0a = x0[tac], x0b = x0[tbc];
+    const float x0a = x0[tac], x0b = x0[tbc];
+    const float xa = xc[tac] - fmaxf(x0a, BLANK_FLOOR), xb = xc[tbc] - fmaxf(x0b, BLANK_FLOOR);
+    const float da = x0a - fmaxf(x0a, BLANK_FLOOR), db0 = x0b - fmaxf(x0b, BLANK_FLOOR);
+    const float bta = (float)(Bu[tac] - Bnew), btb = (float)(Bu[tbc] - Bnew);
     float fa = LOG0F, fb = LOG0F;
     if (ta - 1 >= rs && ta - 1 <= re) fa = rep ? gba : lae(gna, gba);
     if (tb - 1 >= rs && tb - 1 <= re) fb = rep ? gbb : lae(gnb, gbb);
-    Aff ma, mb;                                          // n_t = (n_{t-1} (+) f_t) + x_t(c)
+    Aff ma, mb;                                          // n_t = (n_{t-1} (+) f_t) + x'_t(c)
     ma.a = va ? xa : 0.0f; ma.b = va ? fa + xa : LOG0F;
     mb.a = vb ? xb : 0.0f; mb.b = vb ? fb + xb : LOG0F;
     Aff P = wave_scan_aff(aff_then(ma, mb));
@@ -107,25 +120,26 @@ __device__ __forceinline__ void wave_survivor(const Params& p, int u, int n, int
     const float n_in = lae(E.a + carry_n, E.b);
     const float na = lae(n_in + ma.a, ma.b);
     const float nb = lae(na + mb.a, mb.b);
-    ma.a = va ? x0a : 0.0f; ma.b = va ? n_in + x0a : LOG0F;   // b_t = (n_{t-1} (+) b_{t-1}) + x_t(blank)
-    mb.a = vb ? x0b : 0.0f; mb.b = vb ? na + x0b : LOG0F;
+    ma.a = va ? da : 0.0f; ma.b = va ? n_in + da : LOG0F;     // b_t = (n_{t-1} (+) b_{t-1}) + d_t
+    mb.a = vb ? db0 : 0.0f; mb.b = vb ? na + db0 : LOG0F;
     P = wave_scan_aff(aff_then(ma, mb));
     E.a = dpp_f<0x138, 0xf>(0.0f, P.a); E.b = dpp_f<0x138, 0xf>(LOG0F, P.b);
     const float b_in = lae(E.a + carry_b, E.b);
     const float ba = lae(b_in + ma.a, ma.b);
     const float bb = lae(ba + mb.a, mb.b);
     carry_n = lane_f(nb, 63); carry_b = lane_f(bb, 63);
-    // re-base on the child's own prefix score and store
-    const float rna = (na < LOG0_CLASS) ? LOG0F : na - inc, rnb = (nb < LOG0_CLASS) ? LOG0F : nb - inc;
-    const float rba = (ba < LOG0_CLASS) ? LOG0F : ba - inc, rbb = (bb < LOG0_CLASS) ? LOG0F : bb - inc;
+    // re-base and store
+    const float rna = (na < LOG0_CLASS) ? LOG0F : na - delta, rnb = (nb < LOG0_CLASS) ? LOG0F : nb - delta;
+    const float rba = (ba < LOG0_CLASS) ? LOG0F : ba - delta, rbb = (bb < LOG0_CLASS) ? LOG0F : bb - delta;
     if (va) { cgn[ta] = rna; cgb[ta] = rba; }
     if (vb) { cgn[tb] = rnb; cgb[tb] = rbb; }
-    // first argmax over t >= lo
-    const float ca = (va && ta >= lo) ? rna : LOG0F, cb = (vb && tb >= lo) ? rnb : LOG0F;
-    const float da = (va && ta >= lo) ? rba : LOG0F, db = (vb && tb >= lo) ? rbb : LOG0F;
+    // first argmax over t >= lo of the true variables (stored + B_t; B relative to the child's reference)
+    const bool oka = va && ta >= lo, okb = vb && tb >= lo;
+    const float ca = (oka && rna > LOG0_CLASS) ? rna + bta : LOG0F, cb = (okb && rnb > LOG0_CLASS) ? rnb + btb : LOG0F;
+    const float da2 = (oka && rba > LOG0_CLASS) ? rba + bta : LOG0F, db2 = (okb && rbb > LOG0_CLASS) ? rbb + btb : LOG0F;
     ArgMax xn, xb2;
     xn.v = cb > ca ? cb : ca; xn.t = cb > ca ? tb : ta;
-    xb2.v = db > da ? db : da; xb2.t = db > da ? tb : ta;
+    xb2.v = db2 > da2 ? db2 : da2; xb2.t = db2 > da2 ? tb : ta;
     xn = wave_argmax(xn); xb2 = wave_argmax(xb2);
     if (xn.v > LOG0_CLASS && xn.v > best_n) { best_n = xn.v; arg_n = xn.t; }
     if (xb2.v > LOG0_CLASS && xb2.v > best_b) { best_b = xb2.v; arg_b = xb2.t; }
@@ -208,11 +222,12 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
   __shared__ int s_sel[MAX_BEAM];          // entry index of the new beam's slot n
   // old slots' records
   __shared__ int o_live[MAX_BEAM], o_n[MAX_BEAM], o_stp[MAX_BEAM], o_tau[MAX_BEAM], o_tau_end[MAX_BEAM];
-  __shared__ int o_rs[MAX_BEAM], o_re[MAX_BEAM], o_last[MAX_BEAM], o_ws[MAX_BEAM], o_we[MAX_BEAM];
+  __shared__ int o_rs[MAX_BEAM], o_re[MAX_BEAM], o_last[MAX_BEAM], o_ws[MAX_BEAM], o_we[MAX_BEAM], o_ref[MAX_BEAM];
   __shared__ long long o_cells[MAX_BEAM];
   __shared__ double o_je[MAX_BEAM], o_hatt[MAX_BEAM], o_off[MAX_BEAM];
   __shared__ int s_fin;
   __shared__ int s_ntau[MAX_BEAM], s_ntau_end[MAX_BEAM];   // time indices of the new hypotheses
+  __shared__ float s_delta[MAX_BEAM];                      // by how much each new hypothesis was re-based
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int u = blockIdx.x, Wb = p.Wb;
@@ -227,7 +242,7 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
     o_live[tid] = p.h_live[cur][h]; o_n[tid] = p.grp_n[h]; o_stp[tid] = p.stopped[h];
     o_tau[tid] = p.h_tau[cur][h]; o_tau_end[tid] = p.h_tau_end[cur][h];
     o_rs[tid] = p.h_rs[cur][h]; o_re[tid] = p.h_re[cur][h]; o_last[tid] = p.h_last[cur][h];
-    o_ws[tid] = p.win_s[h]; o_we[tid] = p.win_e[h];
+    o_ws[tid] = p.win_s[h]; o_we[tid] = p.win_e[h]; o_ref[tid] = p.h_ref[cur][h];
     o_cells[tid] = p.grp_cells[h];
     o_je[tid] = p.joint_eos[h]; o_hatt[tid] = p.h_att[cur][h]; o_off[tid] = p.h_off[cur][h];
   }
@@ -326,14 +341,15 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
     SurvivorIn in;
     in.par = par; in.tok = s_tok[e]; in.inc = s_inc[e];
     in.s = o_ws[par]; in.en = o_we[par]; in.rs = o_rs[par]; in.re = o_re[par];
-    in.ptau = o_tau[par]; in.ptau_end = o_tau_end[par]; in.plast = o_last[par];
+    in.ptau = o_tau[par]; in.ptau_end = o_tau_end[par]; in.plast = o_last[par]; in.pref = o_ref[par];
     int arg_n, arg_b;
-    wave_survivor(p, u, n, cur, in, arg_n, arg_b);
+    float delta;
+    wave_survivor(p, u, n, cur, in, arg_n, arg_b, delta);
     if (lane == 0) {
       p.h_tau[nxt][h0 + n] = arg_n; p.h_tau_end[nxt][h0 + n] = arg_b;
       p.out_tau[h0 + n] = arg_n; p.out_tau_end[h0 + n] = arg_b;
       p.trie_tau[trie_l + n] = arg_n;
-      s_ntau[n] = arg_n; s_ntau_end[n] = arg_b;
+      s_ntau[n] = arg_n; s_ntau_end[n] = arg_b; s_delta[n] = delta;
     }
   }
   lds_barrier();                       // (the survivors' state stores stay in flight)
@@ -349,7 +365,8 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
       p.h_live[nxt][h] = fin ? 0 : 1;
       p.h_last[nxt][h] = tok;
       p.h_rs[nxt][h] = o_ws[par]; p.h_re[nxt][h] = o_we[par];
-      p.h_off[nxt][h] = o_off[par] + (double)s_inc[e];
+      p.h_off[nxt][h] = o_off[par] + (double)s_delta[n];
+      p.h_ref[nxt][h] = o_tau[par];
       p.h_att[nxt][h] = o_hatt[par] + (double)s_att[e];
       p.h_joint[nxt][h] = s_J[e];
       if (p.win_union && !fin) {                 // this hypothesis's share of the next step's window
@@ -387,7 +404,7 @@ __global__ __launch_bounds__(BLOCK) void k_select_split(Params p, int l, int cur
   __shared__ int s_tok[MAXE];
   __shared__ float s_inc[MAXE], s_att[MAXE];
   __shared__ int o_live[MAX_BEAM], o_n[MAX_BEAM], o_stp[MAX_BEAM], o_tau[MAX_BEAM], o_tau_end[MAX_BEAM];
-  __shared__ int o_rs[MAX_BEAM], o_re[MAX_BEAM], o_last[MAX_BEAM], o_ws[MAX_BEAM], o_we[MAX_BEAM];
+  __shared__ int o_rs[MAX_BEAM], o_re[MAX_BEAM], o_last[MAX_BEAM], o_ws[MAX_BEAM], o_we[MAX_BEAM], o_ref[MAX_BEAM];
   __shared__ long long o_cells[MAX_BEAM];
   __shared__ double o_je[MAX_BEAM], o_hatt[MAX_BEAM], o_off[MAX_BEAM];
   __shared__ int s_pick[2];                // entry ranked n, entry ranked 0
@@ -408,7 +425,7 @@ __global__ __launch_bounds__(BLOCK) void k_select_split(Params p, int l, int cur
     o_live[tid] = p.h_live[cur][h]; o_n[tid] = p.grp_n[h]; o_stp[tid] = p.stopped[h];
     o_tau[tid] = p.h_tau[cur][h]; o_tau_end[tid] = p.h_tau_end[cur][h];
     o_rs[tid] = p.h_rs[cur][h]; o_re[tid] = p.h_re[cur][h]; o_last[tid] = p.h_last[cur][h];
-    o_ws[tid] = p.win_s[h]; o_we[tid] = p.win_e[h];
+    o_ws[tid] = p.win_s[h]; o_we[tid] = p.win_e[h]; o_ref[tid] = p.h_ref[cur][h];
     o_cells[tid] = p.grp_cells[h];
     o_je[tid] = p.joint_eos[h]; o_hatt[tid] = p.h_att[cur][h]; o_off[tid] = p.h_off[cur][h];
   }
@@ -486,9 +503,10 @@ __global__ __launch_bounds__(BLOCK) void k_select_split(Params p, int l, int cur
       SurvivorIn in;
       in.par = par; in.tok = s_tok[e]; in.inc = s_inc[e];
       in.s = o_ws[par]; in.en = o_we[par]; in.rs = o_rs[par]; in.re = o_re[par];
-      in.ptau = o_tau[par]; in.ptau_end = o_tau_end[par]; in.plast = o_last[par];
+      in.ptau = o_tau[par]; in.ptau_end = o_tau_end[par]; in.plast = o_last[par]; in.pref = o_ref[par];
       int arg_n, arg_b;
-      wave_survivor(p, u, n, cur, in, arg_n, arg_b);
+      float delta;
+      wave_survivor(p, u, n, cur, in, arg_n, arg_b, delta);
       if (lane == 0) {
         p.h_tau[nxt][h] = arg_n; p.h_tau_end[nxt][h] = arg_b;
         p.out_tau[h] = arg_n; p.out_tau_end[h] = arg_b;
@@ -497,7 +515,8 @@ __global__ __launch_bounds__(BLOCK) void k_select_split(Params p, int l, int cur
         p.trie_parent[trie_l + n] = par; p.trie_token[trie_l + n] = in.tok;
         p.h_last[nxt][h] = in.tok;
         p.h_rs[nxt][h] = in.s; p.h_re[nxt][h] = in.en;
-        p.h_off[nxt][h] = o_off[par] + (double)in.inc;
+        p.h_off[nxt][h] = o_off[par] + (double)delta;
+        p.h_ref[nxt][h] = in.ptau;
         p.h_att[nxt][h] = o_hatt[par] + (double)s_att[e];
         p.h_joint[nxt][h] = s_J[e];
       }

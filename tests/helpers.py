@@ -88,12 +88,12 @@ class GpuDecoder:
 
 
 def lockstep_decode(w, ctc, lens, peek=True, check_utts=None, max_steps=None, progress=None,
-                    att_fn=None, gpu_att_fn=None):
+                    att_fn=None, gpu_att_fn=None, eps=1e-4):
     """Decode the batch on the GPU with host-generated attention rows, validating every step of
     the utterances in check_utts (default: all) against the oracle.  Returns (report, results)."""
     U, Wb = len(lens), w["beam"]
     check = list(range(U)) if check_utts is None else list(check_utts)
-    ls = Lockstep([ctc[u, :lens[u]] for u in check], orc_cfg_from(w), utt_ids=check)
+    ls = Lockstep([ctc[u, :lens[u]] for u in check], orc_cfg_from(w), eps=eps, utt_ids=check)
     dec = GpuDecoder(w, ctc, lens)
     try:
         basis = gen.prefix_hash([])
