@@ -25,7 +25,8 @@ def run_sampled(workload, sample, over=None):
     if over:
         w.update(over)
     b = bench.Batch(w, poll_every=8)
-    U, Wb, K = b.U, b.Wb, w["cand_k"]
+    U, Wb = b.U, b.Wb
+    K = w["cand_k"] if 0 < w["cand_k"] < w["vocab"] - 2 else w["vocab"] - 2
     xs = [b.d_ctc[u, :b.lens[u]].cpu().numpy() for u in sample]
     ls = Lockstep(xs, orc_cfg_from(w), utt_ids=sample)
     g = lambda p, shape, dt: m.view(p, shape, dt).cpu().numpy()
@@ -84,4 +85,25 @@ def test_cfg3_one_batch_of_meeting_segments():
     finally:
         gen.workload_lengths = orig
     print(rep)
+    assert rep["max_score_err"] < 1e-4 and rep["max_ctc_err"] < 1e-4
+
+
+def test_cfg4b_full_size_sampled_utterances():
+    """U=256 utterances of 1500 frames, beam 20, top-60, window 80/80: the throughput-bound launch
+    shape (5120 score work-groups, one-work-group-per-utterance select), two utterances followed
+    through all of their ~350 steps."""
+    rep, b = run_sampled("cfg4b", [0, 201])
+    print(rep, "decode steps", b.n_steps, "cells", b.cells)
+    assert rep["max_score_err"] < 1e-4 and rep["max_ctc_err"] < 1e-4
+    assert rep["utt_steps"] > 500
+
+
+def test_cfg4a_full_vocabulary_first_steps():
+    """U=256, T=1500, beam 20, every id a candidate (4998 per hypothesis), no window: the shape whose
+    bound is the ALUs.  The oracle needs seconds per step and utterance here, so one utterance is
+    followed and the decode is capped at five steps (utterances are independent: the others run the
+    same steps)."""
+    rep, b = run_sampled("cfg4a", [77], over=dict(max_len_ratio=0.0, max_len_abs=5))
+    print(rep, "decode steps", b.n_steps, "cells", b.cells)
+    assert b.n_steps == 5 and rep["utt_steps"] == 5
     assert rep["max_score_err"] < 1e-4 and rep["max_ctc_err"] < 1e-4
