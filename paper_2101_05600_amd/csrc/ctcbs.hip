@@ -13,6 +13,7 @@
 #include "k_finalize.h"
 #include "k_ingest.h"
 #include "k_score.h"
+#include "k_score_dense.h"
 #include "k_select.h"
 
 static thread_local int g_last_hip = 0;
@@ -40,6 +41,8 @@ struct ctcbs {
   int32_t known_finished;
   size_t score_smem_bytes;
   int score_block, score_lpc, select_block;
+  int dense_nit, dense_nch;   // all-candidates score kernel: float4 per lane and column (0: not used), chunks per utterance
+  size_t dense_smem_bytes;
   // result staging
   int32_t *d_tokens, *d_frames, *d_ntok, *d_flags;
   float* d_score;
@@ -246,6 +249,16 @@ static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens)
   if (K <= h->score_block) off += (size_t)K * 32 + 8;
   sm.wp_max = p.Tp;
   h->score_smem_bytes = off;
+  // all-candidates kernel: needs the f terms of all beam slots in LDS and a column window in registers
+  h->dense_nit = 0; h->dense_nch = 1; h->dense_smem_bytes = (size_t)Wb * p.Tp * 4;
+  if (!restricted && !(c.end_flags & CTCBS_END_EOS_RUN) && !c.att_is_logits && !c.win_union &&
+      h->dense_smem_bytes <= 150 * 1024 && p.Tp <= 2048) {
+    h->dense_nit = p.Tp <= 256 ? 1 : (p.Tp <= 512 ? 2 : (p.Tp <= 1024 ? 4 : (p.Tp <= 1536 ? 6 : 8)));
+    // enough work-groups to cover the chip, but at least a few dozen candidates each
+    int nch = (256 + U - 1) / U;
+    const int most = K / 32 > 1 ? K / 32 : 1;
+    h->dense_nch = nch < 1 ? 1 : (nch > most ? most : nch);
+  }
   if (off > 160 * 1024) return CTCBS_EINVAL;
   int nw = Wb < 16 ? Wb : 16;
   h->select_block = 64 * (nw <= 4 ? 4 : (nw <= 8 ? 8 : 16));
@@ -283,6 +296,18 @@ static hipError_t launch_score(ctcbs* h, const float* att, int l) {
   return hipGetLastError();
 }
 
+template <int NIT>
+static hipError_t launch_dense(ctcbs* h, const float* att, int l) {
+  if (h->dense_smem_bytes > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute((const void*)k_score_dense<1024, NIT>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->dense_smem_bytes);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((k_score_dense<1024, NIT>), dim3(h->p.U * h->dense_nch), dim3(1024), h->dense_smem_bytes,
+                     h->stream, h->p, att, l, h->cur, h->dense_nch);
+  return hipGetLastError();
+}
+
 extern "C" int ctcbs_step(ctcbs_t* h, const float* d_att_logp, ctcbs_step_out_t* out) {
   if (!h || !d_att_logp) return CTCBS_EINVAL;
   if (h->known_finished >= h->p.U || h->step >= h->l_cap) return CTCBS_DONE;
@@ -295,10 +320,19 @@ extern "C" int ctcbs_step(ctcbs_t* h, const float* d_att_logp, ctcbs_step_out_t*
   }
   // 16 lanes x 2 float4 per candidate cover windows of up to 128 frames without a second
   // trip to memory; unrestricted windows use whole waves, 4 float4 (1024 frames) in flight
-  hipError_t e = (h->score_lpc == 16) ? launch_score<256, 16, 3, 2>(h, d_att_logp, l)
-                                       : launch_score<256, 64, 2, 4>(h, d_att_logp, l);
+  hipError_t e;
+  switch (h->dense_nit) {                 // every id a candidate: one work-group serves all beam slots
+    case 1: e = launch_dense<1>(h, d_att_logp, l); break;
+    case 2: e = launch_dense<2>(h, d_att_logp, l); break;
+    case 4: e = launch_dense<4>(h, d_att_logp, l); break;
+    case 6: e = launch_dense<6>(h, d_att_logp, l); break;
+    case 8: e = launch_dense<8>(h, d_att_logp, l); break;
+    default:
+      e = (h->score_lpc == 16) ? launch_score<256, 16, 3, 2>(h, d_att_logp, l)
+                               : launch_score<256, 64, 2, 4>(h, d_att_logp, l);
+  }
   HIPCHK(e);
-  if (h->p.K > h->score_block) {
+  if (h->dense_nit || h->p.K > h->score_block) {
     hipLaunchKernelGGL((k_group_top<256>), dim3(h->p.U * h->p.Wb), dim3(256), 0, h->stream, h->p, h->cur);
     HIPCHK(hipGetLastError());
   }
