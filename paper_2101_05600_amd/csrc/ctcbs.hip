@@ -333,7 +333,10 @@ extern "C" int ctcbs_step(ctcbs_t* h, const float* d_att_logp, ctcbs_step_out_t*
   }
   HIPCHK(e);
   if (h->dense_nit || h->p.K > h->score_block) {
-    hipLaunchKernelGGL((k_group_top<256>), dim3(h->p.U * h->p.Wb), dim3(256), 0, h->stream, h->p, h->cur);
+    if (h->p.K <= 1024 * 8)
+      hipLaunchKernelGGL((k_group_top_regs<1024, 8>), dim3(h->p.U * h->p.Wb), dim3(1024), 0, h->stream, h->p, h->cur);
+    else
+      hipLaunchKernelGGL((k_group_top<256>), dim3(h->p.U * h->p.Wb), dim3(256), 0, h->stream, h->p, h->cur);
     HIPCHK(hipGetLastError());
   }
   if (ev) HIPCHK(hipEventRecord(ev[1], h->stream));

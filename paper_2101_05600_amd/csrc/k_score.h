@@ -693,3 +693,59 @@ __global__ __launch_bounds__(BLOCK) void k_group_top(Params p, int cur) {
   }
   if (tid == 0) p.grp_n[grp] = n;
 }
+
+// The same list for candidate sets of up to BLOCK * EPT ids, from registers: every thread loads
+// its share of the joint scores once, as 64-bit keys (order-preserving image of the score whose
+// 13 lowest mantissa bits carry 8191 - candidate index: larger score first, then the smaller
+// index = the smaller token id; scores equal to within 2^-39 relative count as equal); each of
+// the Wb rounds is then a block-wide maximum of keys and the owner retires the winner.
+template <int BLOCK, int EPT>
+__global__ __launch_bounds__(BLOCK) void k_group_top_regs(Params p, int cur) {
+  constexpr int NW = BLOCK / 64;
+  __shared__ unsigned long long s_k[2][NW];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int grp = blockIdx.x, u = grp / p.Wb, K = p.K;
+  if (p.finished[u] || !p.h_live[cur][grp]) return;      // the score kernel already wrote grp_n = 0
+  if (p.stopped[grp]) { if (tid == 0) p.grp_n[grp] = 0; return; }
+  const double* J = p.cand_joint + (size_t)grp * K;
+  unsigned long long key[EPT];
+#pragma unroll
+  for (int k = 0; k < EPT; ++k) {
+    const int c = tid + k * BLOCK;
+    const double v = c < K ? J[c] : LOG0D;
+    unsigned long long kk = 0ull;                           // not a competitor
+    if (v > (double)LOG0_CLASS) {                           // (false for NaN)
+      const unsigned long long b = (unsigned long long)__double_as_longlong(v);
+      kk = (((b >> 63) ? ~b : (b | 0x8000000000000000ull)) & ~0x1FFFull) | (unsigned long long)(0x1FFF - c);
+    }
+    key[k] = kk;
+  }
+  int n = 0;
+  for (int r = 0; r < p.Wb; ++r) {
+    unsigned long long best = key[0];
+#pragma unroll
+    for (int k = 1; k < EPT; ++k) best = key[k] > best ? key[k] : best;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const unsigned long long ob = __shfl_xor(best, o);
+      best = ob > best ? ob : best;
+    }
+    if (lane == 0) s_k[r & 1][w] = best;
+    lds_barrier();                                          // (two buffers: one barrier per round is enough)
+    best = s_k[r & 1][0];
+#pragma unroll
+    for (int i = 1; i < NW; ++i) best = s_k[r & 1][i] > best ? s_k[r & 1][i] : best;
+    if (best == 0ull) break;                                // uniform: no finite candidate left
+    const int c = 0x1FFF - (int)(best & 0x1FFFull);
+#pragma unroll
+    for (int k = 0; k < EPT; ++k)
+      if (key[k] == best) key[k] = 0ull;                    // only its owner holds this key
+    if (tid == 0) {
+      const size_t o = (size_t)grp * p.Wb + r, g = (size_t)grp * K + c;
+      p.grp_J[o] = J[c]; p.grp_ci[o] = c; p.grp_tok[o] = p.cand_id[g];
+      p.grp_inc[o] = p.cand_inc[g]; p.grp_att[o] = p.cand_att[g];
+    }
+    ++n;
+  }
+  if (tid == 0) p.grp_n[grp] = n;
+}

@@ -99,3 +99,13 @@ def test_degenerate_posteriors():
     rep, res = lockstep_decode(w, ctc, lens)
     assert rep["max_score_err"] < 1e-4
     assert res["ntok"][0] == 0                              # the empty transcript
+
+
+def test_very_large_unrestricted_vocabulary():
+    """Every id a candidate on a vocabulary beyond what the register-resident list builder holds
+    (more than 8192 candidates per hypothesis): the all-candidates score kernel with the
+    block-wide arg-max list builder."""
+    w = small("cfg1", n_utt=2, t_lo=25, t_hi=40, vocab=9001, beam=3, cand_k=0, win_m1=-1, win_m2=-1,
+              end_flags=3, max_len_abs=7)
+    rep, res = run(w)
+    assert rep["utt_steps"] >= 8
