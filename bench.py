@@ -360,6 +360,23 @@ def main():
         for ln in open(tpath):
             if ln.startswith("traffic_bytes_per_launch:"):
                 traffic = float(ln.split(":")[1])
+    if restricted:
+        roof = {"bound": "hbm", "kernel": "k_score", "achieved": ach, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": traffic,
+                "avg_launch_us": score_ms * 1e3 / max(n_prof, 1),
+                "algorithmic_bytes_per_launch": bytes_score / max(n_prof, 1),
+                "select_kernel_avg_us": select_ms * 1e3 / max(n_prof, 1)}
+    else:
+        # every id a candidate: the beam slots of an utterance share each posterior column, bytes fall
+        # to 4/Wb per term and the bound is the plain ALUs.  Per term one fused multiply-add, one
+        # exp2, one add = 4 flop; the exp2 issues at quarter rate, so the three instructions take 6
+        # issue slots: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz / 6 = 6.55e12 terms/s = 26.2 TFLOP/s is
+        # the most this instruction mix can reach (the chip's 157.3 TFLOP/s needs an FMA in every slot)
+        tf = 4.0 * b.cells / (score_ms * 1e-3) / 1e12
+        peak = 256 * 4 * 16 * 2.4e9 / 6.0 * 4.0 / 1e12
+        roof = {"bound": "alu", "kernel": "k_score_dense", "achieved": tf, "peak": peak, "unit": "TFLOP/s",
+                "frac": tf / peak, "traffic": None, "avg_launch_us": score_ms * 1e3 / max(n_prof, 1),
+                "flop_per_term": 4, "select_kernel_avg_us": select_ms * 1e3 / max(n_prof, 1)}
     line = {
         "metric": "CTC prefix-score cells/sec (utt·beam·cand·frame) + utterances/sec at B=64",
         "value": b.cells / (dt / a.steps), "unit": "cells/s",
@@ -374,11 +391,7 @@ def main():
                    "decode_steps": b.n_steps, "cells_per_decode": b.cells,
                    "poll_every": a.poll_every, "batches_in_flight": a.inflight,
                    "host_threads": a.threads if a.inflight > 1 else 1},
-        "roofline": {"bound": "hbm", "kernel": "k_score", "achieved": ach, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": traffic,
-                     "avg_launch_us": score_ms * 1e3 / max(n_prof, 1),
-                     "algorithmic_bytes_per_launch": bytes_score / max(n_prof, 1),
-                     "select_kernel_avg_us": select_ms * 1e3 / max(n_prof, 1)},
+        "roofline": roof,
     }
     if a.inflight == 1 and not a.no_offline:
         # context, not the headline: a queue of copies of the same batch, 8 in flight (own handle and

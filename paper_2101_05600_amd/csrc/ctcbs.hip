@@ -332,6 +332,7 @@ extern "C" int ctcbs_step(ctcbs_t* h, const float* d_att_logp, ctcbs_step_out_t*
                                : launch_score<256, 64, 2, 4>(h, d_att_logp, l);
   }
   HIPCHK(e);
+  if (ev) HIPCHK(hipEventRecord(ev[1], h->stream));       // (the list builder below counts as selection)
   if (h->dense_nit || h->p.K > h->score_block) {
     if (h->p.K <= 1024 * 8)
       hipLaunchKernelGGL((k_group_top_regs<1024, 8>), dim3(h->p.U * h->p.Wb), dim3(1024), 0, h->stream, h->p, h->cur);
@@ -339,7 +340,6 @@ extern "C" int ctcbs_step(ctcbs_t* h, const float* d_att_logp, ctcbs_step_out_t*
       hipLaunchKernelGGL((k_group_top<256>), dim3(h->p.U * h->p.Wb), dim3(256), 0, h->stream, h->p, h->cur);
     HIPCHK(hipGetLastError());
   }
-  if (ev) HIPCHK(hipEventRecord(ev[1], h->stream));
   // Small batches leave most compute units idle in the one-work-group-per-utterance form: there the
   // split form (one work-group per new beam slot, each ranking the utterance's lists itself) is
   // faster (measured: U=64 and U=128 at beam 10).  Large batches fill the chip either way and the
