@@ -345,7 +345,7 @@ extern "C" int ctcbs_step(ctcbs_t* h, const float* d_att_logp, ctcbs_step_out_t*
   // faster (measured: U=64 and U=128 at beam 10).  Large batches fill the chip either way and the
   // Wb-fold repeated ranking only costs (U=256 at beam 20: three times slower).  The batch-union
   // window needs the utterance's hypotheses in one place.
-  const bool split = !h->p.win_union && h->p.U * h->p.Wb <= 2048 && h->p.Wb <= 16;
+  const bool split = !h->p.win_union && h->p.U * h->p.Wb <= 2048;
   if (split) {
     hipLaunchKernelGGL((k_select_split<256>), dim3(h->p.U * h->p.Wb), dim3(256), 0, h->stream, h->p, l, h->cur);
   } else switch (h->select_block) {
