@@ -1,7 +1,7 @@
 // Score kernel: one work-group per (utterance, beam slot) hypothesis g.
 //   1. candidate pre-selection: the K ids with the largest attention log-prob, ties to the
-//      smaller id.  The row never goes through LDS: every lane keeps its float4 loads as
-//      order-preserving keys in registers.  Fast path: a pivot L that is provably not above
+//      smaller id.  The row never goes through LDS: every lane keeps its float4 loads in
+//      registers.  Fast path: a pivot L that is provably not above
 //      the K-th largest value (every wave contributes the ceil(K/#waves)-th largest of its
 //      lanes' maxima, found by bisection on the upper key bits), then an exact ranking of the
 //      few values >= L.  Rows that do not fit the registers, or with so many values >= L that

@@ -1,4 +1,5 @@
-// Select kernel: one work-group per utterance.  Algorithm 2 from TopB on:
+// Select kernels (k_select: one work-group per utterance; k_select_split, further down: one per
+// new beam slot).  Algorithm 2 from TopB on:
 //   - merge the groups' best-first lists into the utterance's new beam (TopB / GatherB),
 //     total order (joint desc, parent slot asc, token asc);
 //   - the "p > best_score" test that moves g.<eos> into the ended set, forced ending at the
