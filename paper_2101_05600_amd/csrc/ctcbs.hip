@@ -4,6 +4,8 @@
 
 #include <hip/hip_runtime.h>
 #include <math.h>
+#include <map>
+#include <mutex>
 #include <new>
 #include <stdlib.h>
 #include <string.h>
@@ -284,13 +286,29 @@ extern "C" int ctcbs_create(const ctcbs_config_t* cfg, const float* d_ctc_logp, 
   return CTCBS_OK;
 }
 
+// Kernels that want more than 64 KB of dynamic LDS need the attribute raised first.  It belongs to
+// the kernel, not to a handle: it is only ever raised (handles of different sizes, on different
+// threads, share it), and only when a launch needs more than what is already allowed.
+static hipError_t allow_lds(const void* kernel, size_t bytes) {
+  if (bytes <= 64 * 1024) return hipSuccess;
+  static std::mutex mu;
+  static std::map<const void*, size_t> allowed;
+  std::lock_guard<std::mutex> lock(mu);
+  try {
+    size_t& have = allowed[kernel];
+    if (bytes <= have) return hipSuccess;
+    hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) have = bytes;
+    return e;
+  } catch (...) {                                          // (the map could not grow)
+    return hipErrorOutOfMemory;
+  }
+}
+
 template <int BLOCK, int LPC, int CB, int IT>
 static hipError_t launch_score(ctcbs* h, const float* att, int l) {
-  if (h->score_smem_bytes > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute((const void*)k_score<BLOCK, LPC, CB, IT>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->score_smem_bytes);
-    if (e != hipSuccess) return e;
-  }
+  hipError_t ea = allow_lds((const void*)k_score<BLOCK, LPC, CB, IT>, h->score_smem_bytes);
+  if (ea != hipSuccess) return ea;
   hipLaunchKernelGGL((k_score<BLOCK, LPC, CB, IT>), dim3(h->p.U * h->p.Wb), dim3(BLOCK), h->score_smem_bytes,
                      h->stream, h->p, h->sm, att, l, h->cur);
   return hipGetLastError();
@@ -298,11 +316,8 @@ static hipError_t launch_score(ctcbs* h, const float* att, int l) {
 
 template <int NIT>
 static hipError_t launch_dense(ctcbs* h, const float* att, int l) {
-  if (h->dense_smem_bytes > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute((const void*)k_score_dense<1024, NIT>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->dense_smem_bytes);
-    if (e != hipSuccess) return e;
-  }
+  hipError_t ea = allow_lds((const void*)k_score_dense<1024, NIT>, h->dense_smem_bytes);
+  if (ea != hipSuccess) return ea;
   hipLaunchKernelGGL((k_score_dense<1024, NIT>), dim3(h->p.U * h->dense_nch), dim3(1024), h->dense_smem_bytes,
                      h->stream, h->p, att, l, h->cur, h->dense_nch);
   return hipGetLastError();
