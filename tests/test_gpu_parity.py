@@ -450,3 +450,47 @@ def test_run_many_reproduces_single_decodes():
     finally:
         for d in decs:
             d.close()
+
+
+def test_executor_error_paths():
+    """A failing callback stops the executor with its error; the handles stay usable."""
+    import torch
+    import paper_2101_05600_amd as m
+    w = small("cfg1", n_utt=2, t_lo=30, t_hi=50, vocab=300, beam=3, cand_k=8, win_m1=10, win_m2=10, end_flags=3)
+    lens, ctc = make_inputs(w)
+    decs = [GpuDecoder(dict(w, stream=torch.cuda.Stream().cuda_stream), ctc, lens, poll_every=2) for _ in range(2)]
+    try:
+        d_ctc = torch.from_numpy(np.ascontiguousarray(ctc)).cuda()
+        rows = torch.zeros((2, 3, 300), dtype=torch.float32, device="cuda")
+        rows[:] = torch.log_softmax(torch.arange(300, dtype=torch.float32, device="cuda") * 0.01, dim=0)
+
+        class Boom(RuntimeError):
+            pass
+
+        def bad_job(job, slot, h, phase):
+            if job == 1 and phase == m.JOB_LOAD:
+                raise Boom("no such batch")
+            if phase == m.JOB_LOAD:
+                m.ctcbs_reset(h, d_ctc, lens)
+        with pytest.raises(Boom):
+            m.ctcbs_run_queue([d.h for d in decs], 4, bad_job, att_fn=lambda job, step, prev: rows, n_threads=2)
+
+        def bad_att(index, step, prev):
+            if step == 3:
+                raise Boom("decoder failed")
+            return rows
+        for d in decs:
+            m.ctcbs_reset(d.h, d_ctc, lens)
+        with pytest.raises(m.CtcbsError):
+            m.ctcbs_run_many([d.h for d in decs], att_fn=bad_att)
+        with pytest.raises(m.CtcbsError):
+            m.ctcbs_run_many([d.h for d in decs], replay=[[rows.data_ptr()]] * 2, n_threads=0)
+        # after the failures: reset and decode normally, both handles give the same result
+        for d in decs:
+            m.ctcbs_reset(d.h, d_ctc, lens)
+        m.ctcbs_run_many([d.h for d in decs], att_fn=lambda i, step, prev: rows, n_threads=1)
+        r0, r1 = decs[0].finalize(), decs[1].finalize()
+        assert np.array_equal(r0[0], r1[0]) and np.array_equal(r0[2], r1[2]) and (r0[1] > 0).all()
+    finally:
+        for d in decs:
+            d.close()
