@@ -216,8 +216,8 @@ template <int BLOCK>
 __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
   constexpr int NW = BLOCK / 64;
   constexpr int MAXE = MAX_BEAM * MAX_BEAM;
-  constexpr int EPT = (MAXE + BLOCK - 1) / BLOCK;
   __shared__ double s_J[MAXE];
+  __shared__ __align__(16) unsigned long long s_key[MAXE + 8];
   __shared__ int s_par[MAXE], s_ci[MAXE], s_tok[MAXE];
   __shared__ float s_inc[MAXE], s_att[MAXE];
   __shared__ int s_sel[MAX_BEAM];          // entry index of the new beam's slot n
@@ -257,64 +257,54 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
     if (lane == 0) { st_best = us->best_score; st_n = us->n_ended; st_cnt = us->cnt_tau_T; }
     if (lane < p.end_m) { ring_sc = us->ring_score[lane]; ring_tag = us->ring_tag[lane]; }
   }
-  // group lists: entry i = j * Wb + r of this utterance (Wb * Wb <= 1024 entries)
-  double eJ[EPT]; int eci[EPT], etok[EPT]; float einc[EPT], eatt[EPT];
-#pragma unroll
-  for (int k = 0; k < EPT; ++k) {
-    const int i = tid + k * BLOCK;
-    if (i < Wb * Wb) {
+  // group lists: entry i = j * Wb + r of this utterance (group j's r-th best; Wb * Wb <= 1024 entries),
+  // each with a 64-bit sort key: the score as an order-preserving integer whose 10 lowest mantissa
+  // bits are replaced by the entry's position (earlier position = larger key).  One integer comparison
+  // then gives a strict total order: joint score descending and, among scores equal to within 2^-42
+  // relative (far inside the tolerance to which scores are meaningful), parent slot, then token,
+  // ascending.  Entries past a list's length and the padding get keys below every score.
+  const int NE = Wb * Wb;
+  for (int i = tid; i < NE + 8; i += BLOCK) {
+    unsigned long long key = 0ull;
+    if (i < NE) {
+      const int j = i / Wb, r = i - j * Wb;
       const size_t o = h0 * Wb + i;
-      eJ[k] = p.grp_J[o]; eci[k] = p.grp_ci[o]; etok[k] = p.grp_tok[o];
-      einc[k] = p.grp_inc[o]; eatt[k] = p.grp_att[o];
+      const int nj = p.grp_n[h0 + j];
+      const double Jv = p.grp_J[o];
+      s_par[i] = j; s_ci[i] = p.grp_ci[o]; s_tok[i] = p.grp_tok[o];
+      s_inc[i] = p.grp_inc[o]; s_att[i] = p.grp_att[o];
+      s_J[i] = Jv;
+      const unsigned long long bb = (unsigned long long)__double_as_longlong(Jv);
+      const unsigned long long k = (bb >> 63) ? ~bb : (bb | 0x8000000000000000ull);
+      key = r < nj ? ((k & ~1023ull) | (unsigned long long)(1023 - i)) : (unsigned long long)(1023 - i) >> 1;
     }
+    s_key[i] = key;
   }
   if (tid < MAX_BEAM) s_sel[tid] = -1;
   lds_barrier();
   TRACE_POINT(p, u, 9);
-  // every thread sums the list lengths itself (independent LDS reads, no serial section)
   int ne = 0;
-  int base_of[EPT];
-#pragma unroll
-  for (int k = 0; k < EPT; ++k) base_of[k] = 0;
 #pragma unroll 8
-  for (int j = 0; j < Wb; ++j) {
-    const int nj = o_n[j];
-#pragma unroll
-    for (int k = 0; k < EPT; ++k) base_of[k] += (j < (tid + k * BLOCK) / Wb) ? nj : 0;
-    ne += nj;
-  }
-#pragma unroll
-  for (int k = 0; k < EPT; ++k) {
-    const int i = tid + k * BLOCK;
-    if (i < Wb * Wb) {
-      const int j = i / Wb, r = i % Wb;
-      if (r < o_n[j]) {
-        const int e = base_of[k] + r;
-        s_J[e] = eJ[k]; s_par[e] = j; s_ci[e] = eci[k]; s_tok[e] = etok[k];
-        s_inc[e] = einc[k]; s_att[e] = eatt[k];
+  for (int j = 0; j < Wb; ++j) ne += o_n[j];
+  // ---- rank: L lanes per entry, each comparing against every L-th quad of keys ----------------
+  {
+    const int L = NE <= BLOCK / 8 ? 8 : (NE <= BLOCK / 4 ? 4 : (NE <= BLOCK / 2 ? 2 : 1));
+    const int part = tid & (L - 1);
+    const int quads = (NE + 3) >> 2;                       // (the padding holds zeros)
+    const ulonglong2* s_k2 = (const ulonglong2*)s_key;
+    for (int e0 = 0; e0 < NE; e0 += BLOCK / L) {
+      const int e = e0 + tid / L;
+      const unsigned long long me = s_key[min(e, NE)];
+      int rank = 0;
+      for (int q4 = part; q4 < quads; q4 += L) {            // four keys per trip, two independent reads
+        const ulonglong2 v = s_k2[2 * q4], v2 = s_k2[2 * q4 + 1];
+        rank += (int)(v.x > me) + (int)(v.y > me) + (int)(v2.x > me) + (int)(v2.y > me);
       }
+      if (L >= 2) rank += dpp_i<0xB1, 0xf>(0, rank);       // quad_perm [1,0,3,2]
+      if (L >= 4) rank += dpp_i<0x4E, 0xf>(0, rank);       // quad_perm [2,3,0,1]
+      if (L == 8) rank += dpp_i<0x104, 0xf>(0, rank);      // row_shl:4: the first lane of the eight gets the other quad's sum
+      if (part == 0 && e < NE && me > 1023ull && rank < Wb) s_sel[rank] = e;
     }
-  }
-  lds_barrier();
-  // ---- rank (total order: joint desc, parent slot asc, candidate index asc = token asc) -----
-  // eight lanes per entry, each comparing against an eighth of the list
-  for (int e0 = 0; e0 < ne; e0 += BLOCK / 8) {
-    const int e = e0 + (tid >> 3), part = tid & 7;
-    const bool have = e < ne;
-    const double me = have ? s_J[e] : LOG0D;
-    // equal scores: entries are stored in (parent slot, token) order, so the position decides
-    int rank = 0, rank2 = 0;
-    for (int o = part; o < ne; o += 16) {                  // two independent chains of LDS reads
-      const double v = s_J[o];
-      const double v2 = o + 8 < ne ? s_J[o + 8] : -1.0e300;
-      rank += (v > me) || (v == me && o < e);
-      rank2 += (v2 > me) || (v2 == me && o + 8 < e);
-    }
-    rank += rank2;
-    rank += __shfl_xor(rank, 1);
-    rank += __shfl_xor(rank, 2);
-    rank += __shfl_xor(rank, 4);
-    if (part == 0 && have && rank < Wb) s_sel[rank] = e;
   }
   lds_barrier();
 
