@@ -61,9 +61,9 @@ __device__ __forceinline__ ArgMax wave_argmax(ArgMax x) {
 }
 
 // Forward variables of one new hypothesis (parent slot `par` extended by `tok`) over the
-// parent's window, by one wave: two scans of affine maps in the (logaddexp, +) semiring, 128
-// frames per pass (each lane owns two consecutive frames, composes their two maps, the wave
-// scans the composed maps, and the lane then replays its own two frames).
+// parent's window, by one wave: two scans of affine maps in the (logaddexp, +) semiring (each lane
+// owns a few consecutive frames, composes their maps, the wave scans the composed maps, and the
+// lane then replays its own frames).
 // The recurrence runs on the stored form of the variables (per-frame reference B_t taken out,
 // see Params::Bcum): with x'_t(c) = x_t(c) - max(x_t(blank), floor) and d_t = x_t(blank) -
 // max(x_t(blank), floor) (zero unless the floor cut),
@@ -77,8 +77,10 @@ struct SurvivorIn {
   int par, tok, s, en, rs, re, ptau, ptau_end, plast, pref;
   float inc;
 };
-__device__ __forceinline__ void wave_survivor(const Params& p, int u, int n, int cur, const SurvivorIn& in,
-                                              int& arg_n, int& arg_b, float& delta_out) {
+// FPL consecutive frames per lane, 64 * FPL frames per pass.
+template <int FPL>
+__device__ __forceinline__ void wave_survivor_fpl(const Params& p, int u, int n, int cur, const SurvivorIn& in,
+                                                  int& arg_n, int& arg_b, float& delta_out) {
   const int lane = threadIdx.x & 63;
   const size_t h0 = (size_t)u * p.Wb;
   const size_t hp = h0 + in.par;
@@ -99,52 +101,79 @@ __device__ __forceinline__ void wave_survivor(const Params& p, int u, int n, int
   float carry_n = LOG0F, carry_b = LOG0F;
   float best_n = LOG0F, best_b = LOG0F;
   arg_n = in.ptau; arg_b = in.ptau_end;
-  for (int base = s; base <= en; base += 128) {
-    const int ta = base + 2 * lane, tb = ta + 1;
-    const bool va = ta <= en, vb = tb <= en;
-    const int tac = min(ta, en), tbc = min(tb, en);      // clamped: loads are unconditional
-    const float gna = pgn[max(tac - 1, 0)], gba = pgb[max(tac - 1, 0)];
-    const float gnb = pgn[tbc - 1], gbb = pgb[tbc - 1];
-    const float x0a = x0[tac], x0b = x0[tbc];
-    const float xa = xc[tac] - fmaxf(x0a, BLANK_FLOOR), xb = xc[tbc] - fmaxf(x0b, BLANK_FLOOR);
-    const float da = x0a - fmaxf(x0a, BLANK_FLOOR), db0 = x0b - fmaxf(x0b, BLANK_FLOOR);
-    const float bta = (float)(Bu[tac] - Bnew), btb = (float)(Bu[tbc] - Bnew);
-    float fa = LOG0F, fb = LOG0F;
-    if (ta - 1 >= rs && ta - 1 <= re) fa = rep ? gba : lae(gna, gba);
-    if (tb - 1 >= rs && tb - 1 <= re) fb = rep ? gbb : lae(gnb, gbb);
-    Aff ma, mb;                                          // n_t = (n_{t-1} (+) f_t) + x'_t(c)
-    ma.a = va ? xa : 0.0f; ma.b = va ? fa + xa : LOG0F;
-    mb.a = vb ? xb : 0.0f; mb.b = vb ? fb + xb : LOG0F;
-    Aff P = wave_scan_aff(aff_then(ma, mb));
+  for (int base = s; base <= en; base += 64 * FPL) {
+    int t[FPL]; bool v[FPL]; float bt[FPL];
+    Aff mn[FPL];                                         // n_t = (n_{t-1} (+) f_t) + x'_t(c)
+    float d[FPL];
+#pragma unroll
+    for (int k = 0; k < FPL; ++k) {
+      t[k] = base + FPL * lane + k;
+      v[k] = t[k] <= en;
+      const int tc = min(t[k], en);                      // clamped: loads are unconditional
+      const float gn = pgn[max(tc - 1, 0)], gb = pgb[max(tc - 1, 0)];
+      const float x0v = x0[tc];
+      const float x = xc[tc] - fmaxf(x0v, BLANK_FLOOR);
+      d[k] = x0v - fmaxf(x0v, BLANK_FLOOR);
+      bt[k] = (float)(Bu[tc] - Bnew);
+      float f = LOG0F;
+      if (t[k] - 1 >= rs && t[k] - 1 <= re) f = rep ? gb : lae(gn, gb);
+      mn[k].a = v[k] ? x : 0.0f; mn[k].b = v[k] ? f + x : LOG0F;
+    }
+    Aff C = mn[0];
+#pragma unroll
+    for (int k = 1; k < FPL; ++k) C = aff_then(C, mn[k]);
+    Aff P = wave_scan_aff(C);
     Aff E;                                               // maps of all earlier lanes
     E.a = dpp_f<0x138, 0xf>(0.0f, P.a); E.b = dpp_f<0x138, 0xf>(LOG0F, P.b);
     const float n_in = lae(E.a + carry_n, E.b);
-    const float na = lae(n_in + ma.a, ma.b);
-    const float nb = lae(na + mb.a, mb.b);
-    ma.a = va ? da : 0.0f; ma.b = va ? n_in + da : LOG0F;     // b_t = (n_{t-1} (+) b_{t-1}) + d_t
-    mb.a = vb ? db0 : 0.0f; mb.b = vb ? na + db0 : LOG0F;
-    P = wave_scan_aff(aff_then(ma, mb));
+    float nv[FPL];
+    nv[0] = lae(n_in + mn[0].a, mn[0].b);
+#pragma unroll
+    for (int k = 1; k < FPL; ++k) nv[k] = lae(nv[k - 1] + mn[k].a, mn[k].b);
+    Aff mb[FPL];                                         // b_t = (n_{t-1} (+) b_{t-1}) + d_t
+#pragma unroll
+    for (int k = 0; k < FPL; ++k) {
+      const float nprev = k == 0 ? n_in : nv[k - 1];
+      mb[k].a = v[k] ? d[k] : 0.0f; mb[k].b = v[k] ? nprev + d[k] : LOG0F;
+    }
+    C = mb[0];
+#pragma unroll
+    for (int k = 1; k < FPL; ++k) C = aff_then(C, mb[k]);
+    P = wave_scan_aff(C);
     E.a = dpp_f<0x138, 0xf>(0.0f, P.a); E.b = dpp_f<0x138, 0xf>(LOG0F, P.b);
     const float b_in = lae(E.a + carry_b, E.b);
-    const float ba = lae(b_in + ma.a, ma.b);
-    const float bb = lae(ba + mb.a, mb.b);
-    carry_n = lane_f(nb, 63); carry_b = lane_f(bb, 63);
-    // re-base and store
-    const float rna = (na < LOG0_CLASS) ? LOG0F : na - delta, rnb = (nb < LOG0_CLASS) ? LOG0F : nb - delta;
-    const float rba = (ba < LOG0_CLASS) ? LOG0F : ba - delta, rbb = (bb < LOG0_CLASS) ? LOG0F : bb - delta;
-    if (va) { cgn[ta] = rna; cgb[ta] = rba; }
-    if (vb) { cgn[tb] = rnb; cgb[tb] = rbb; }
-    // first argmax over t >= lo of the true variables (stored + B_t; B relative to the child's reference)
-    const bool oka = va && ta >= lo, okb = vb && tb >= lo;
-    const float ca = (oka && rna > LOG0_CLASS) ? rna + bta : LOG0F, cb = (okb && rnb > LOG0_CLASS) ? rnb + btb : LOG0F;
-    const float da2 = (oka && rba > LOG0_CLASS) ? rba + bta : LOG0F, db2 = (okb && rbb > LOG0_CLASS) ? rbb + btb : LOG0F;
-    ArgMax xn, xb2;
-    xn.v = cb > ca ? cb : ca; xn.t = cb > ca ? tb : ta;
-    xb2.v = db2 > da2 ? db2 : da2; xb2.t = db2 > da2 ? tb : ta;
-    xn = wave_argmax(xn); xb2 = wave_argmax(xb2);
+    float bv[FPL];
+    bv[0] = lae(b_in + mb[0].a, mb[0].b);
+#pragma unroll
+    for (int k = 1; k < FPL; ++k) bv[k] = lae(bv[k - 1] + mb[k].a, mb[k].b);
+    carry_n = lane_f(nv[FPL - 1], 63); carry_b = lane_f(bv[FPL - 1], 63);
+    // re-base, store, and the lane's own first argmax over t >= lo of the true variables
+    // (stored + B_t; B relative to the child's reference)
+    ArgMax xn, xb;
+    xn.v = LOG0F; xn.t = t[0]; xb.v = LOG0F; xb.t = t[0];
+#pragma unroll
+    for (int k = 0; k < FPL; ++k) {
+      const float rn = (nv[k] < LOG0_CLASS) ? LOG0F : nv[k] - delta;
+      const float rb = (bv[k] < LOG0_CLASS) ? LOG0F : bv[k] - delta;
+      if (v[k]) { cgn[t[k]] = rn; cgb[t[k]] = rb; }
+      const bool ok = v[k] && t[k] >= lo;
+      const float cn = (ok && rn > LOG0_CLASS) ? rn + bt[k] : LOG0F;
+      const float cb = (ok && rb > LOG0_CLASS) ? rb + bt[k] : LOG0F;
+      if (cn > xn.v) { xn.v = cn; xn.t = t[k]; }           // (strict: the earlier frame keeps a tie)
+      if (cb > xb.v) { xb.v = cb; xb.t = t[k]; }
+    }
+    xn = wave_argmax(xn); xb = wave_argmax(xb);
     if (xn.v > LOG0_CLASS && xn.v > best_n) { best_n = xn.v; arg_n = xn.t; }
-    if (xb2.v > LOG0_CLASS && xb2.v > best_b) { best_b = xb2.v; arg_b = xb2.t; }
+    if (xb.v > LOG0_CLASS && xb.v > best_b) { best_b = xb.v; arg_b = xb.t; }
   }
+}
+
+// windows of up to 128 frames: two frames per lane, one pass; longer ones: four per lane (a pass
+// costs about 1.4 times as much and covers twice as many frames)
+__device__ __forceinline__ void wave_survivor(const Params& p, int u, int n, int cur, const SurvivorIn& in,
+                                              int& arg_n, int& arg_b, float& delta_out) {
+  if (in.en - in.s + 1 <= 128) wave_survivor_fpl<2>(p, u, n, cur, in, arg_n, arg_b, delta_out);
+  else wave_survivor_fpl<4>(p, u, n, cur, in, arg_n, arg_b, delta_out);
 }
 
 // Ended set and ENDDETECT of one utterance, by one wave (lane j = old slot j).  `mine`: slot j
