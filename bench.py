@@ -356,7 +356,7 @@ def main():
     # plain copy): taken from the committed counter summary, not measurable from inside this process
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"k_score_{a.workload}_traffic.txt")
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and a.utts == 0:           # the counters were read at the workload's own size
         for ln in open(tpath):
             if ln.startswith("traffic_bytes_per_launch:"):
                 traffic = float(ln.split(":")[1])
