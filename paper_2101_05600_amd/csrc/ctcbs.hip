@@ -155,8 +155,15 @@ static int ingest(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens) {
   }
   HIPCHK(hipMemsetAsync(p.grp_n, 0, sizeof(int32_t) * UW, st));
   HIPCHK(hipMemsetAsync(p.stopped, 0, sizeof(int32_t) * UW, st));
-  dim3 tg((p.V + 63) / 64, (c.t_max + 4 + 63) / 64, U);
-  hipLaunchKernelGGL(k_transpose, tg, dim3(256), 0, st, p, d_ctc_logp);
+  {
+    const int nvt = (p.V + 255) / 256, ntt = (c.t_max + 5 + 31) / 32;   // stored indices 0 .. t_max + 4
+    const int n_tiles = nvt * ntt, per_xcd = (n_tiles + 7) / 8;
+    const dim3 tg(8 * per_xcd, U);
+    if (p.V % 4 == 0 && ((uintptr_t)d_ctc_logp & 15) == 0)
+      hipLaunchKernelGGL(k_transpose<true>, tg, dim3(256), 0, st, p, d_ctc_logp, nvt, n_tiles, per_xcd);
+    else
+      hipLaunchKernelGGL(k_transpose<false>, tg, dim3(256), 0, st, p, d_ctc_logp, nvt, n_tiles, per_xcd);
+  }
   HIPCHK(hipGetLastError());
   hipLaunchKernelGGL(k_init_state, dim3(U), dim3(64), 0, st, p);
   HIPCHK(hipGetLastError());
@@ -176,7 +183,7 @@ static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens)
   const bool restricted = c.cand_k > 0 && c.cand_k < V - 2;
   const int K = restricted ? c.cand_k : V - 2;
   p.U = U; p.V = V; p.Wb = Wb; p.K = K;
-  p.Tp = ((c.t_max + 1 + 3) / 4) * 4 + 4;       // frames 0..t_max plus slack for aligned float4 reads
+  p.Tp = ((c.t_max + 5 + 31) / 32) * 32;        // frames 0..t_max plus slack for aligned float4 reads; rows of whole 128-byte lines
   p.t_max = c.t_max; p.blank_id = c.blank_id; p.eos_id = c.eos_id; p.restricted = restricted ? 1 : 0;
   p.win_m1 = c.win_m1; p.win_m2 = c.win_m2; p.end_flags = c.end_flags;
   p.end_m = (c.end_m >= 1 && c.end_m <= MAX_END_M) ? c.end_m : 1;

@@ -3,32 +3,71 @@
 #include "common.h"
 
 // CTC log-posteriors [U][t_max][V] (frame-major, as an encoder emits them) -> token-major
-// xT[u][k][t], t = 1..T_u, so that one candidate's frames are contiguous.  64x64 tiles
-// through LDS; frames at and beyond T_u are never read.  Index 0 and the four entries after
-// T_u are set to zero: aligned float4 loads of a window may touch them (their terms are
-// masked through the f array, which needs finite values there).
-__global__ __launch_bounds__(256) void k_transpose(Params p, const float* __restrict__ x) {
-  __shared__ float tile[64][65];
-  const int u = blockIdx.z;
+// xT[u][k][t], t = 1..T_u, so that one candidate's frames are contiguous.  A work-group moves a
+// tile of 256 tokens x 32 stored frames through LDS: 1 KB contiguous per frame on the way in
+// (float4 per lane when rows are 16-byte aligned: VEC), whole aligned 128-byte lines per token on
+// the way out (rows of xT start on line boundaries, and the tile is cut in STORED frame indices,
+// which are one more than the 0-based input frame).  Frames at and beyond T_u are never read.
+// Index 0 and the entries after T_u up to the end of their tile (at least four) are set to zero:
+// aligned float4 loads of a window may touch them (their terms are masked through the f array,
+// which needs finite values there).  Work-groups go round-robin over the eight XCDs; tiles are
+// numbered so that each XCD walks through one contiguous eighth of the utterance's tiles, token
+// tiles of a 32-frame band one after the other: the lines two neighbouring tiles share are then
+// fetched into one L2 instead of two, and each XCD streams through its own region of memory.
+// Which eighth an XCD takes rotates with the utterance, so that short utterances (whose last
+// eighths are empty) do not leave the same XCDs idle.
+template <bool VEC>
+__global__ __launch_bounds__(256) void k_transpose(Params p, const float* __restrict__ x, int nvt, int n_tiles,
+                                                   int per_xcd) {
+  __shared__ __attribute__((aligned(16))) float tile[32][260];
+  const int u = blockIdx.y;
   const int T = p.lens[u];
-  const int t0 = blockIdx.y * 64, v0 = blockIdx.x * 64;
-  if (t0 >= T + 4) return;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int g = (((int)blockIdx.x - u) & 7) * per_xcd + (blockIdx.x >> 3);
+  if (g >= n_tiles) return;
+  const int jt = g / nvt, vt = g - jt * nvt;
+  const int d0 = jt * 32;                                // first stored frame index of the tile
+  if (d0 > T + 4) return;
+  const int v0 = vt * 256;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const float* src = x + (size_t)u * p.t_max * p.V;
-#pragma unroll 4
-  for (int i = 0; i < 16; ++i) {
-    int tt = t0 + ty * 16 + i, vv = v0 + tx;
-    tile[ty * 16 + i][tx] = (tt < T && vv < p.V) ? fmaxf(src[(size_t)tt * p.V + vv], LOG0F) : 0.0f;
+  float4 r[8];
+  const int v = v0 + 4 * lane;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int tt = d0 - 1 + w * 8 + i;                   // 0-based input frame of stored index tt + 1
+    r[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    if (tt >= 0 && tt < T) {
+      const float* row = src + (size_t)tt * p.V + v;
+      if (VEC) {
+        if (v < p.V) r[i] = *(const float4*)row;         // V is a multiple of 4 here
+      } else {
+        if (v + 0 < p.V) r[i].x = row[0];
+        if (v + 1 < p.V) r[i].y = row[1];
+        if (v + 2 < p.V) r[i].z = row[2];
+        if (v + 3 < p.V) r[i].w = row[3];
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    float4 c;
+    c.x = fmaxf(r[i].x, LOG0F); c.y = fmaxf(r[i].y, LOG0F); c.z = fmaxf(r[i].z, LOG0F); c.w = fmaxf(r[i].w, LOG0F);
+    *(float4*)&tile[w * 8 + i][4 * lane] = c;
   }
   __syncthreads();
   float* dst = p.xT + (size_t)u * p.V * p.Tp;
-#pragma unroll 4
-  for (int i = 0; i < 16; ++i) {
-    int vv = v0 + ty * 16 + i, tt = t0 + tx;
-    if (vv < p.V) {
-      if (tt < T) dst[(size_t)vv * p.Tp + tt + 1] = tile[tx][ty * 16 + i];
-      else if (tt < T + 4) dst[(size_t)vv * p.Tp + tt + 1] = 0.0f;
-      if (tt == 0) dst[(size_t)vv * p.Tp] = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int q = i * 256 + threadIdx.x;
+    const int vl = q >> 3, t4 = (q & 7) * 4;             // eight lanes cover one token's 32 frames
+    const int d = d0 + t4;
+    if (v0 + vl < p.V && d < p.Tp) {                     // Tp is a multiple of 4
+      float4 o;
+      o.x = (d + 0 >= 1 && d + 0 <= T) ? tile[t4 + 0][vl] : 0.0f;
+      o.y = (d + 1 <= T) ? tile[t4 + 1][vl] : 0.0f;
+      o.z = (d + 2 <= T) ? tile[t4 + 2][vl] : 0.0f;
+      o.w = (d + 3 <= T) ? tile[t4 + 3][vl] : 0.0f;
+      *(float4*)(dst + (size_t)(v0 + vl) * p.Tp + d) = o;
     }
   }
 }
