@@ -121,7 +121,10 @@ typedef struct {
  * vocab, utterance pitch t_max*vocab; frames at and beyond h_lens[u] are never read), and
  * set every utterance's beam to the single empty hypothesis.  The posteriors are copied
  * (token-major) before the call returns, so the caller may release d_ctc_logp afterwards.
- * On failure *out is NULL.
+ * 0 <= h_lens[u] <= t_max; a length of 0 marks an unused slot of the batch (a last batch that
+ * is not full): it is finished from the start, holds no hypothesis (its d_live flags are 0),
+ * none of its rows is read, and ctcbs_finalize reports it with no tokens, score -1e30 and
+ * flag 1.  On failure *out is NULL.
  */
 int ctcbs_create(const ctcbs_config_t* cfg, const float* d_ctc_logp, const int32_t* h_lens,
                  ctcbs_t** out);

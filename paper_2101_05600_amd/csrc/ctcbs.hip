@@ -134,9 +134,10 @@ static int ingest(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens) {
   Params& p = h->p;
   const int U = c.n_utt;
   std::vector<int32_t> lens(h_lens, h_lens + U), lmax(U);
-  int l_cap = 1;
+  int l_cap = 1, n_empty = 0;
   for (int u = 0; u < U; ++u) {
-    if (lens[u] < 1 || lens[u] > c.t_max) return CTCBS_EINVAL;
+    if (lens[u] < 0 || lens[u] > c.t_max) return CTCBS_EINVAL;
+    if (lens[u] == 0) { lmax[u] = 1; ++n_empty; continue; }   // an unused slot of the batch
     lmax[u] = step_cap(&c, lens[u]);
     if (lmax[u] > l_cap) l_cap = lmax[u];
   }
@@ -165,12 +166,12 @@ static int ingest(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens) {
       hipLaunchKernelGGL(k_transpose<false>, tg, dim3(256), 0, st, p, d_ctc_logp, nvt, n_tiles, per_xcd);
   }
   HIPCHK(hipGetLastError());
-  hipLaunchKernelGGL(k_init_state, dim3(U), dim3(64), 0, st, p);
+  hipLaunchKernelGGL(k_init_state, dim3(U), dim3(64), 0, st, p, n_empty);
   HIPCHK(hipGetLastError());
-  h->step = 0; h->cur = 0; h->known_finished = 0;
+  h->step = 0; h->cur = 0; h->known_finished = n_empty;
   h->profiling = false; h->ev_used = 0;
   h->throttle_k = 0; h->throttle_armed[0] = h->throttle_armed[1] = false;
-  *h->h_flag = 0;
+  *h->h_flag = n_empty;
   HIPCHK(hipStreamSynchronize(st));
   return CTCBS_OK;
 }

@@ -78,8 +78,10 @@ __global__ __launch_bounds__(256) void k_transpose(Params p, const float* __rest
 // BLANK_FLOOR) is also the reference B_t every stored forward variable is taken relative to: the
 // empty hypothesis's stored blank variable is therefore 0 at every frame (minus whatever the
 // floor cut off: log0 from the first frame on whose blank probability is zero).
-// One wave per utterance.
-__global__ __launch_bounds__(64) void k_init_state(Params p) {
+// One wave per utterance.  An utterance of no frames is an unused slot of the batch: it counts as
+// finished from the start (n_empty of them, counted by the host), holds no hypothesis and takes
+// part in nothing.
+__global__ __launch_bounds__(64) void k_init_state(Params p, int n_empty) {
   const int u = blockIdx.x, lane = threadIdx.x;
   const int T = p.lens[u];
   const size_t hyp0 = (size_t)u * p.Wb;
@@ -106,11 +108,11 @@ __global__ __launch_bounds__(64) void k_init_state(Params p) {
   for (int t = T + 1 + lane; t < p.Tp; t += 64) Bu[t] = carry;   // (never weighted: keeps reads defined)
   for (int j = lane; j < p.Wb; j += 64) {
     size_t h = hyp0 + j;
-    p.h_live[0][h] = (j == 0); p.h_last[0][h] = -1;
+    p.h_live[0][h] = (j == 0 && T > 0); p.h_last[0][h] = -1;
     p.h_rs[0][h] = 0; p.h_re[0][h] = T; p.h_tau[0][h] = 0; p.h_tau_end[0][h] = 0; p.h_ref[0][h] = 0;
     p.h_off[0][h] = 0.0; p.h_att[0][h] = 0.0; p.h_joint[0][h] = 0.0;
     p.h_live[1][h] = 0;
-    p.out_live[h] = (j == 0); p.out_parent[h] = 0; p.out_token[h] = -1; p.out_score[h] = 0.0f;
+    p.out_live[h] = (j == 0 && T > 0); p.out_parent[h] = 0; p.out_token[h] = -1; p.out_score[h] = 0.0f;
     p.out_tau[h] = 0; p.out_tau_end[h] = 0; p.out_eos_added[h] = 0; p.out_stopped[h] = 0;
     p.trie_parent[h] = 0; p.trie_token[h] = -1; p.trie_tau[h] = 0;   // level 0: the empty hypothesis
   }
@@ -118,11 +120,11 @@ __global__ __launch_bounds__(64) void k_init_state(Params p) {
     UttState s;
     s.best_score = LOG0D; s.fb_score = LOG0D;
     for (int i = 0; i < MAX_END_M; ++i) { s.ring_score[i] = LOG0D; s.ring_tag[i] = -1; }
-    s.n_ended = 0; s.best_step = 0; s.best_slot = 0; s.cnt_tau_T = 0; s.finished_step = 0; s.pad = 0;
+    s.n_ended = 0; s.best_step = 0; s.best_slot = 0; s.cnt_tau_T = 0; s.finished_step = T > 0 ? 0 : -1; s.pad = 0;
     p.utt[u] = s;
-    p.finished[u] = 0;
+    p.finished[u] = T > 0 ? 0 : 1;
     p.cells[u] = 0ull;
     p.groups[u] = 0ull;
-    if (u == 0) *p.n_finished = 0;
+    if (u == 0) *p.n_finished = n_empty;
   }
 }

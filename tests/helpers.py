@@ -78,7 +78,7 @@ class GpuDecoder:
                     ctc_eos=pk(m.PEEK_CTC_EOS).reshape(U, Wb), joint_eos=pk(m.PEEK_JOINT_EOS).reshape(U, Wb))
 
     def finalize(self, frames=False):
-        cap = int(max(oracle.lib().orc_lmax(ctypes.byref(orc_cfg_from(self.w)), int(t)) for t in self.lens))
+        cap = int(max(oracle.lib().orc_lmax(ctypes.byref(orc_cfg_from(self.w)), int(t)) for t in self.lens if t > 0))
         return self.m.ctcbs_finalize(self.h, self.U, cap, want_frames=frames)
 
     def close(self):

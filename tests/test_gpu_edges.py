@@ -109,3 +109,43 @@ def test_very_large_unrestricted_vocabulary():
               end_flags=3, max_len_abs=7)
     rep, res = run(w)
     assert rep["utt_steps"] >= 8
+
+
+@pytest.mark.parametrize("variant", ["windowed", "batch_window", "all_candidates"])
+def test_unused_slots_of_a_batch(variant):
+    """Length 0 marks an unused slot (a last batch that is not full): it is finished from the
+    start, holds no hypothesis, costs nothing and reports an empty result; the other utterances
+    decode exactly as they do in a full batch (every step against the oracle)."""
+    kw = dict(windowed=dict(cand_k=10, win_m1=6, win_m2=6, end_flags=7, eos_run=3),
+              batch_window=dict(cand_k=10, win_m1=6, win_m2=6, end_flags=7, eos_run=3, win_union=1),
+              all_candidates=dict(cand_k=0, win_m1=-1, win_m2=-1, end_flags=3))[variant]
+    w = small("cfg1", vocab=48, beam=3, max_len_ratio=0.4, **kw)
+    lens = np.asarray([0, 37, 0, 0, 90, 12, 0], np.int32)
+    ctc = gen.workload_ctc(w, np.maximum(lens, 1))          # the rows of an unused slot are never read
+    ctc[lens == 0] = np.nan
+    used = [u for u in range(len(lens)) if lens[u] > 0]
+    seen_live = []
+    rep, res = lockstep_decode(w, ctc, lens, check_utts=used,
+                               progress=lambda step, out: seen_live.append(out["live"][lens == 0].any()
+                                                                           or not out["finished"][lens == 0].all()))
+    assert rep["max_score_err"] < 1e-4 and rep["max_ctc_err"] < 1e-4, rep
+    assert res["cells"] == int(res["oracle_cells"])
+    assert not any(seen_live)
+    empty = lens == 0
+    assert (res["ntok"][empty] == 0).all() and (res["flags"][empty] == 1).all() and (res["score"][empty] < -1e29).all()
+
+
+def test_batch_of_unused_slots_only():
+    import torch
+    import paper_2101_05600_amd as m
+    w = small("cfg1", vocab=48, beam=3, cand_k=10, win_m1=6, win_m2=6, end_flags=7, eos_run=3)
+    cfg = m.make_config(n_utt=3, t_max=20, **{k: v for k, v in w.items() if k != "n_utt"})
+    d_ctc = torch.full((3, 20, 48), float("nan"), device="cuda")
+    h = m.ctcbs_create(cfg, d_ctc, np.zeros(3, np.int32))
+    try:
+        att = torch.full((3, 3, 48), float("nan"), device="cuda")
+        assert m.ctcbs_step(h, att, m.StepOut()) == m.DONE
+        tok, nt, sc, frm, fl = m.ctcbs_finalize(h, 3, 4)
+        assert (nt == 0).all() and (fl == 1).all() and (sc < -1e29).all()
+    finally:
+        m.ctcbs_destroy(h)
