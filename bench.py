@@ -49,6 +49,11 @@ def parse():
                          "settings (Table 'batch decoding': M1 = 5, M2 in {inf, 60, 40, 20}), the per-hypothesis "
                          "and the batch-wide window, and print a table (terms, time, agreement with the "
                          "unrestricted decode)")
+    ap.add_argument("--job", action="store_true",
+                    help="instead of the benchmark line: decode a whole offline job shaped like the workload's "
+                         "recordings (cfg3: 32 synthetic long recordings cut into segments, sorted by length, "
+                         "batches of the workload's size, --inflight batches in flight on --threads host threads) "
+                         "and print one JSON line for the job")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (known traffic, for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -58,14 +63,14 @@ def parse():
 class Batch:
     """Device-resident synthetic batch plus the recorded attention rows of its decode."""
 
-    def __init__(self, w, poll_every):
+    def __init__(self, w, poll_every, lens=None, t_max=None):
         import torch
         import gen
         import paper_2101_05600_amd as m
         self.torch, self.gen, self.m, self.w = torch, gen, m, w
         self.U, self.Wb, self.V = w["n_utt"], w["beam"], w["vocab"]
-        self.lens = gen.workload_lengths(w)
-        self.t_max = int(self.lens.max())
+        self.lens = gen.workload_lengths(w) if lens is None else np.asarray(lens, np.int32)
+        self.t_max = int(self.lens.max()) if t_max is None else int(t_max)
         self.poll_every = poll_every
         self.stream = torch.cuda.current_stream().cuda_stream
         self.d_lens = torch.from_numpy(self.lens).cuda()
@@ -292,6 +297,83 @@ def sweep(a):
         print(f"| {r[0]} | {r[1]:.3e} | {r[2]} | {r[3]:.2f} | {100 * r[4]:.1f} % | {r[5]:.2e} |")
 
 
+def run_job(a):
+    """A whole offline job (Sec. 4.2 / 4.4 of the paper: segments sorted by length, decoded batch by
+    batch, several batches in flight).  Segment lengths come from the synthetic recordings of the
+    workload; every batch has its own posteriors and its own recorded attention rows, all resident in
+    HBM before the timed region; the last batch is filled up with unused slots (length 0)."""
+    import torch
+    import gen
+    import paper_2101_05600_amd as m
+    w = gen.workload(a.workload)
+    if a.utts > 0:
+        w["n_utt"] = a.utts
+    U = w["n_utt"]
+    seg = gen.segments(w["seed"])
+    order, begin = m.ctcbs_plan_batches(seg, U)
+    t_max = int(seg.max())
+    batches = []
+    for j in range(len(begin) - 1):
+        ids = order[begin[j]:begin[j + 1]]
+        lens = np.zeros(U, np.int32)
+        lens[:len(ids)] = seg[ids]
+        b = Batch(dict(w, seed=w["seed"] + 7919 * (j + 1)), a.poll_every, lens=lens, t_max=t_max)
+        b.record()
+        batches.append(b)
+    n_slots = max(a.inflight, 1)
+    l_cap = max(b.l_cap for b in batches)
+    streams = [torch.cuda.Stream() for _ in range(n_slots)]
+    hs = []
+    for st in streams:
+        cfg = m.make_config(n_utt=U, t_max=t_max, poll_every=a.poll_every, stream=st.cuda_stream,
+                            **{k: v for k, v in w.items() if k not in ("n_utt", "stream")})
+        hs.append(m.ctcbs_create(cfg, batches[0].d_ctc, batches[0].lens))
+    results = [None] * len(batches)
+
+    def job_fn(job, slot, h, phase):
+        if phase == m.JOB_LOAD:
+            m.ctcbs_reset(h, batches[job].d_ctc, batches[job].lens)
+        else:
+            results[job] = m.ctcbs_finalize(h, U, l_cap)
+
+    def one_pass():
+        m.ctcbs_run_queue(hs, len(batches), job_fn, replay=[b.att_ptr[:b.n_steps] for b in batches],
+                          n_threads=a.threads)
+    try:
+        for _ in range(max(a.warmup, 1)):
+            one_pass()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(a.steps):
+            one_pass()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / a.steps
+    finally:
+        for h in hs:
+            m.ctcbs_destroy(h)
+    for b, r in zip(batches, results):
+        n = int((b.lens > 0).sum())
+        c = min(r[0].shape[1], b.ref[0].shape[1])            # token capacity differs (job-wide / the batch's own)
+        same = (np.array_equal(r[0][:n, :c], b.ref[0][:n, :c]) and np.array_equal(r[1][:n], b.ref[1][:n])
+                and np.array_equal(r[2][:n], b.ref[2][:n]))
+        assert same, "a queued decode did not reproduce the lone decode of its batch"
+    cells = sum(b.cells for b in batches)
+    frames = int(seg.sum())
+    audio_s = frames * 4 / 100.0                  # 4x-subsampled 100 frames/s features
+    print(json.dumps({
+        "metric": "whole offline job: segments/s and prefix-score cells/s", "value": len(seg) / dt,
+        "unit": "segments/s", "cells_per_sec": cells / dt, "job_seconds": dt, "n_gpus": 1, "steps": a.steps,
+        "warmup": max(a.warmup, 1), "higher_is_better": True, "dtype": "f32", "data": "synthetic",
+        "audio_hours": audio_s / 3600.0, "audio_seconds_per_second": audio_s / dt,
+        "config": {"workload": f"{a.workload} job: {len(seg)} segments of {int(seg.min())}-{t_max} frames from 32 "
+                               f"synthetic recordings, sorted by length, {len(batches)} batches of {U} (last one "
+                               f"{int((batches[-1].lens > 0).sum())} used slots), V={w['vocab']}, beam {w['beam']}, "
+                               f"top-{w['cand_k']}, window {w['win_m1']}/{w['win_m2']}; decoding path only "
+                               f"(posteriors and recorded attention rows resident in HBM)",
+                   "batches_in_flight": n_slots, "host_threads": a.threads,
+                   "decode_steps_total": sum(b.n_steps for b in batches), "cells_per_job": cells}}))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -307,6 +389,9 @@ def main():
     m.lib()
     if a.sweep:
         sweep(a)
+        return
+    if a.job:
+        run_job(a)
         return
     w = gen.workload(a.workload)
     if a.utts > 0:

@@ -452,6 +452,62 @@ def test_run_many_reproduces_single_decodes():
             d.close()
 
 
+def test_offline_job_segments_to_batches_to_queue():
+    """The offline recipe end to end on a small scale (Sec. 4.2 and 4.4): a recording is cut into
+    segments of bounded length, the segments are sorted by length and dealt into batches of four (the
+    last one not full: unused slots), and the batches are decoded through the job queue on two
+    handles.  Every batch's lone decode is validated against the oracle step by step; the queue must
+    return exactly those results."""
+    import torch
+    import paper_2101_05600_amd as m
+    seg = np.concatenate([m.ctcbs_hard_segments(431, 40, 75), m.ctcbs_hard_segments(158, 40, 75)])
+    assert seg.sum() == 431 + 158 and seg.max() <= 75
+    order, begin = m.ctcbs_plan_batches(seg, 4)
+    n_b = len(begin) - 1
+    assert n_b == 3 and begin[-1] == len(seg) == 9           # 4 + 4 + 1
+    T = int(seg.max())
+    ws, data, singles, recs = [], [], [], []
+    for j in range(n_b):
+        ids = order[begin[j]:begin[j + 1]]
+        lens = np.zeros(4, np.int32)
+        lens[:len(ids)] = seg[ids]
+        w = small("cfg1", n_utt=4, vocab=300, beam=4, cand_k=12, win_m1=12, win_m2=12, end_flags=7, eos_run=4,
+                  seed=77 + j)
+        ctc = np.full((4, T, 300), np.nan, np.float32)
+        g = gen.workload_ctc(w, np.maximum(lens, 1))
+        for u in range(4):
+            ctc[u, :lens[u]] = g[u, :lens[u]]
+        rows = []
+        rep, res = lockstep_decode(w, ctc, lens, check_utts=[u for u in range(4) if lens[u] > 0],
+                                   gpu_att_fn=lambda a, rows=rows: rows.append(a.copy()) or a)
+        assert rep["max_score_err"] < 1e-4
+        ws.append(w); data.append((torch.from_numpy(ctc).cuda(), lens)); singles.append(res)
+        recs.append([torch.from_numpy(r).cuda() for r in rows])
+    decs = [GpuDecoder(dict(ws[0], stream=torch.cuda.Stream().cuda_stream), data[0][0].cpu().numpy(), data[0][1],
+                       poll_every=3) for _ in range(2)]
+    try:
+        got = [None] * n_b
+        cap = max(r["tokens"].shape[1] for r in singles)
+
+        def job_fn(job, slot, h, phase):
+            if phase == m.JOB_LOAD:
+                m.ctcbs_reset(h, data[job][0], data[job][1])
+            else:
+                got[job] = m.ctcbs_finalize(h, 4, cap)
+        torch.cuda.synchronize()
+        m.ctcbs_run_queue([d.h for d in decs], n_b, job_fn,
+                          replay=[[t.data_ptr() for t in rec] for rec in recs], n_threads=2)
+        for j in range(n_b):
+            tok, nt, sc, frm, fl = got[j]
+            c = singles[j]["tokens"].shape[1]
+            assert np.array_equal(tok[:, :c], singles[j]["tokens"]) and np.array_equal(nt, singles[j]["ntok"])
+            assert np.array_equal(sc, singles[j]["score"]) and np.array_equal(fl, singles[j]["flags"])
+        assert (got[-1][1][1:] == 0).all()                   # the unused slots of the last batch
+    finally:
+        for d in decs:
+            d.close()
+
+
 def test_executor_error_paths():
     """A failing callback stops the executor with its error; the handles stay usable."""
     import torch
