@@ -52,7 +52,8 @@ __global__ __launch_bounds__(256) void k_transpose(Params p, const float* __rest
   for (int i = 0; i < 8; ++i) {
     float4 c;
     c.x = fmaxf(r[i].x, LOG0F); c.y = fmaxf(r[i].y, LOG0F); c.z = fmaxf(r[i].z, LOG0F); c.w = fmaxf(r[i].w, LOG0F);
-    *(float4*)&tile[w * 8 + i][4 * lane] = c;
+    const int t = w * 8 + i;
+    *(float4*)&tile[t][(4 * lane) ^ (((t >> 3) & 3) << 2)] = c;   // (swizzle: see the reads below)
   }
   __syncthreads();
   float* dst = p.xT + (size_t)u * p.V * p.Tp;
@@ -60,13 +61,17 @@ __global__ __launch_bounds__(256) void k_transpose(Params p, const float* __rest
   for (int i = 0; i < 8; ++i) {
     const int q = i * 256 + threadIdx.x;
     const int vl = q >> 3, t4 = (q & 7) * 4;             // eight lanes cover one token's 32 frames
+    // a wave reads 8 tokens x 8 groups of 4 frames; with rows of 260 floats, frames 8 apart would
+    // share banks, so each band of 8 rows keeps its float4 columns in a different order: the lanes
+    // of a wave (of a half wave too) fall on distinct banks
+    const int vs = vl ^ ((t4 >> 3) << 2);
     const int d = d0 + t4;
     if (v0 + vl < p.V && d < p.Tp) {                     // Tp is a multiple of 4
       float4 o;
-      o.x = (d + 0 >= 1 && d + 0 <= T) ? tile[t4 + 0][vl] : 0.0f;
-      o.y = (d + 1 <= T) ? tile[t4 + 1][vl] : 0.0f;
-      o.z = (d + 2 <= T) ? tile[t4 + 2][vl] : 0.0f;
-      o.w = (d + 3 <= T) ? tile[t4 + 3][vl] : 0.0f;
+      o.x = (d + 0 >= 1 && d + 0 <= T) ? tile[t4 + 0][vs] : 0.0f;
+      o.y = (d + 1 <= T) ? tile[t4 + 1][vs] : 0.0f;
+      o.z = (d + 2 <= T) ? tile[t4 + 2][vs] : 0.0f;
+      o.w = (d + 3 <= T) ? tile[t4 + 3][vs] : 0.0f;
       *(float4*)(dst + (size_t)(v0 + vl) * p.Tp + d) = o;
     }
   }
