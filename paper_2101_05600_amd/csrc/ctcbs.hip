@@ -43,6 +43,7 @@ struct ctcbs {
   int32_t known_finished;
   size_t score_smem_bytes;
   int score_block, score_lpc, select_block;
+  bool score_wide;
   int dense_nit, dense_nch;   // all-candidates score kernel: float4 per lane and column (0: not used), chunks per utterance
   size_t dense_smem_bytes;
   // result staging
@@ -249,6 +250,8 @@ static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens)
   h->score_block = 256;
   const bool windowed = c.win_m1 >= 0 && c.win_m2 >= 0 && (c.win_m1 + c.win_m2) <= 448;
   h->score_lpc = windowed ? 16 : 64;
+  // windows beyond 128 frames (16 lanes x 2 float4): four float4 per lane in flight, two candidates at a time
+  h->score_wide = windowed && (c.win_m1 + c.win_m2 + 1 + 3) > 128;
   ScoreSmem& sm = h->sm;
   size_t off = 0;
   sm.off_work = (int32_t)off;
@@ -351,7 +354,8 @@ extern "C" int ctcbs_step(ctcbs_t* h, const float* d_att_logp, ctcbs_step_out_t*
     case 6: e = launch_dense<6>(h, d_att_logp, l); break;
     case 8: e = launch_dense<8>(h, d_att_logp, l); break;
     default:
-      e = (h->score_lpc == 16) ? launch_score<256, 16, 3, 2>(h, d_att_logp, l)
+      e = (h->score_lpc == 16) ? (h->score_wide ? launch_score<256, 16, 2, 4>(h, d_att_logp, l)
+                                                : launch_score<256, 16, 3, 2>(h, d_att_logp, l))
                                : launch_score<256, 64, 2, 4>(h, d_att_logp, l);
   }
   HIPCHK(e);

@@ -268,7 +268,7 @@ __device__ __forceinline__ double block_sum_d(float sum, double* s_d /*[BLOCK / 
 }
 
 template <int BLOCK, int LPC, int CB, int IT>
-__global__ __launch_bounds__(BLOCK, 5) void k_score(Params p, ScoreSmem sm, const float* __restrict__ att,
+__global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p, ScoreSmem sm, const float* __restrict__ att,
                                                  int l, int cur) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ uint32_t s_scan[BLOCK / 64 + 1];
