@@ -373,8 +373,9 @@ extern "C" int ctcbs_step(ctcbs_t* h, const float* d_att_logp, ctcbs_step_out_t*
   // Wb-fold repeated ranking only costs (U=256 at beam 20: three times slower).  The batch-union
   // window needs the utterance's hypotheses in one place.
   const bool split = !h->p.win_union && h->p.U * h->p.Wb <= 2048;
+  const size_t split_lds = (size_t)28 * h->p.Wb * h->p.Wb + 64;
   if (split) {
-    hipLaunchKernelGGL((k_select_split<256>), dim3(h->p.U * h->p.Wb), dim3(256), 0, h->stream, h->p, l, h->cur);
+    hipLaunchKernelGGL((k_select_split<256>), dim3(h->p.U * h->p.Wb), dim3(256), split_lds, h->stream, h->p, l, h->cur);
   } else switch (h->select_block) {
     case 256: hipLaunchKernelGGL((k_select<256>), dim3(h->p.U), dim3(256), 0, h->stream, h->p, l, h->cur); break;
     case 512: hipLaunchKernelGGL((k_select<512>), dim3(h->p.U), dim3(512), 0, h->stream, h->p, l, h->cur); break;

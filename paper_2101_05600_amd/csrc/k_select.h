@@ -416,13 +416,17 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
 // the utterance state is read by slot 0's work-group alone, and "finished before this step"
 // is taken from the step number at which the utterance finished (0 or the current step both
 // mean no).
+// Dynamic LDS: 28 * Wb * Wb + 64 bytes (the list entries).
 template <int BLOCK>
 __global__ __launch_bounds__(BLOCK) void k_select_split(Params p, int l, int cur) {
-  constexpr int MAXE = MAX_BEAM * MAX_BEAM;
-  __shared__ double s_J[MAXE];
-  __shared__ __align__(16) unsigned long long s_key[MAXE + 8];
-  __shared__ int s_tok[MAXE];
-  __shared__ float s_inc[MAXE], s_att[MAXE];
+  static_assert(BLOCK >= 128, "wave 0 and wave 1 have different jobs");
+  extern __shared__ __align__(16) unsigned char split_smem[];
+  const int NE = p.Wb * p.Wb;
+  unsigned long long* s_key = (unsigned long long*)split_smem;        // [NE + 8]
+  double* s_J = (double*)(s_key + NE + 8);                            // [NE]
+  int* s_tok = (int*)(s_J + NE);                                      // [NE]
+  float* s_inc = (float*)(s_tok + NE);                                // [NE]
+  float* s_att = s_inc + NE;                                          // [NE]
   __shared__ int o_live[MAX_BEAM], o_n[MAX_BEAM], o_stp[MAX_BEAM], o_tau[MAX_BEAM], o_tau_end[MAX_BEAM];
   __shared__ int o_rs[MAX_BEAM], o_re[MAX_BEAM], o_last[MAX_BEAM], o_ws[MAX_BEAM], o_we[MAX_BEAM], o_ref[MAX_BEAM];
   __shared__ long long o_cells[MAX_BEAM];
@@ -463,7 +467,6 @@ __global__ __launch_bounds__(BLOCK) void k_select_split(Params p, int l, int cur
   // order: joint score descending, and among scores equal to within 2^-42 relative (far inside
   // the tolerance to which scores are meaningful) parent slot, then token, ascending.  Entries
   // past a list's length and the padding get keys below every score.
-  const int NE = Wb * Wb;
   for (int i = tid; i < NE + 8; i += BLOCK) {
     unsigned long long key = 0ull;
     if (i < NE) {
