@@ -176,6 +176,26 @@ __device__ __forceinline__ void wave_survivor(const Params& p, int u, int n, int
   else wave_survivor_fpl<4>(p, u, n, cur, in, arg_n, arg_b, delta_out);
 }
 
+// How many of the keys s_k2[0 .. 2 * quads) (four per quad, zero padding at the end) exceed `me`,
+// counting every L-th quad from `part` on.  Sixteen keys are fetched before the first is compared, so
+// that the LDS round trips overlap.
+__device__ __forceinline__ int count_greater(const ulonglong2* s_k2, unsigned long long me, int part, int L,
+                                             int quads) {
+  int n = 0, q4 = part;
+  for (; q4 + 3 * L < quads; q4 += 4 * L) {
+    ulonglong2 v[8];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) { v[2 * k] = s_k2[2 * (q4 + k * L)]; v[2 * k + 1] = s_k2[2 * (q4 + k * L) + 1]; }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) n += (int)(v[k].x > me) + (int)(v[k].y > me);
+  }
+  for (; q4 < quads; q4 += L) {
+    const ulonglong2 v = s_k2[2 * q4], v2 = s_k2[2 * q4 + 1];
+    n += (int)(v.x > me) + (int)(v.y > me) + (int)(v2.x > me) + (int)(v2.y > me);
+  }
+  return n;
+}
+
 // Ended set and ENDDETECT of one utterance, by one wave (lane j = old slot j).  `mine`: slot j
 // held a live hypothesis; je / stp / tau_j / cells_j: its eos joint score, eos-run stop, tau and
 // prefix-score terms of this step.  st_* / ring_*: the utterance's state as loaded by lane 0
@@ -324,11 +344,8 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
     for (int e0 = 0; e0 < NE; e0 += BLOCK / L) {
       const int e = e0 + tid / L;
       const unsigned long long me = s_key[min(e, NE)];
-      int rank = 0;
-      for (int q4 = part; q4 < quads; q4 += L) {            // four keys per trip, two independent reads
-        const ulonglong2 v = s_k2[2 * q4], v2 = s_k2[2 * q4 + 1];
-        rank += (int)(v.x > me) + (int)(v.y > me) + (int)(v2.x > me) + (int)(v2.y > me);
-      }
+      const int rank0 = count_greater(s_k2, me, part, L, quads);
+      int rank = rank0;
       if (L >= 2) rank += dpp_i<0xB1, 0xf>(0, rank);       // quad_perm [1,0,3,2]
       if (L >= 4) rank += dpp_i<0x4E, 0xf>(0, rank);       // quad_perm [2,3,0,1]
       if (L == 8) rank += dpp_i<0x104, 0xf>(0, rank);      // row_shl:4: the first lane of the eight gets the other quad's sum
@@ -501,11 +518,8 @@ __global__ __launch_bounds__(BLOCK) void k_select_split(Params p, int l, int cur
     for (int e0 = 0; e0 < NE; e0 += BLOCK / L) {
       const int e = e0 + tid / L;
       const unsigned long long me = s_key[min(e, NE)];
-      int rank = 0;
-      for (int q4 = part; q4 < quads; q4 += L) {            // four keys per trip, two independent reads
-        const ulonglong2 v = s_k2[2 * q4], v2 = s_k2[2 * q4 + 1];
-        rank += (v.x > me) + (v.y > me) + (v2.x > me) + (v2.y > me);
-      }
+      const int rank0 = count_greater(s_k2, me, part, L, quads);
+      int rank = rank0;
       if (L >= 2) rank += dpp_i<0xB1, 0xf>(0, rank);       // quad_perm [1,0,3,2]
       if (L == 4) rank += dpp_i<0x4E, 0xf>(0, rank);       // quad_perm [2,3,0,1]
       if (part == 0 && e < NE && me > 1023ull) {
