@@ -196,6 +196,39 @@ __device__ __forceinline__ int count_greater(const ulonglong2* s_k2, unsigned lo
   return n;
 }
 
+// The lists are sorted, so few of their Wb * Wb entries can reach the new beam.  A lower bound on the
+// Wb-th largest key: the smallest of the first R entries of every non-empty list, R such that those
+// are at least Wb entries (if the lists are too short for that: no bound).  Entries below the bound
+// cannot rank among the first Wb; the others are packed into s_ck (keys) / s_cidx (their entry
+// numbers), followed by zero keys, and only they are ranked against each other: a key carries its
+// entry number, so the rank among them is the rank among all.  s_ck must hold zeros on entry,
+// s_cnt[0..1] zeros and *s_min all ones; both barriers are inside.  Returns how many were packed.
+template <int BLOCK>
+__device__ __forceinline__ int pack_contenders(const unsigned long long* s_key, int NE, int Wb, const int* o_n,
+                                               unsigned long long* s_ck, int* s_cidx, int* s_cnt,
+                                               unsigned long long* s_min) {
+  const int tid = threadIdx.x;
+  int nl = 0;
+#pragma unroll 8
+  for (int j = 0; j < Wb; ++j) nl += (o_n[j] > 0);
+  const int R = nl > 0 ? (Wb + nl - 1) / nl : 0;
+  for (int i = tid; i < NE; i += BLOCK) {
+    const int j = i / Wb, r = i - j * Wb;
+    if (r < R && r < o_n[j]) { atomicMin(s_min, s_key[i]); atomicAdd(&s_cnt[0], 1); }
+  }
+  lds_barrier();
+  const unsigned long long bound = s_cnt[0] >= Wb ? *s_min : 0ull;
+  for (int i = tid; i < NE; i += BLOCK) {
+    const unsigned long long k = s_key[i];
+    if (k > 1023ull && k >= bound) {
+      const int pos = atomicAdd(&s_cnt[1], 1);
+      s_ck[pos] = k; s_cidx[pos] = i;
+    }
+  }
+  lds_barrier();
+  return s_cnt[1];
+}
+
 // Ended set and ENDDETECT of one utterance, by one wave (lane j = old slot j).  `mine`: slot j
 // held a live hypothesis; je / stp / tau_j / cells_j: its eos joint score, eos-run stop, tau and
 // prefix-score terms of this step.  st_* / ring_*: the utterance's state as loaded by lane 0
@@ -270,6 +303,10 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
   __shared__ int s_par[MAXE], s_ci[MAXE], s_tok[MAXE];
   __shared__ float s_inc[MAXE], s_att[MAXE];
   __shared__ int s_sel[MAX_BEAM];          // entry index of the new beam's slot n
+  __shared__ __align__(16) unsigned long long s_ck[MAXE + 8];   // keys of the entries that can reach the new beam
+  __shared__ int s_cidx[MAXE];
+  __shared__ int s_cnt[2];
+  __shared__ unsigned long long s_min;
   // old slots' records
   __shared__ int o_live[MAX_BEAM], o_n[MAX_BEAM], o_stp[MAX_BEAM], o_tau[MAX_BEAM], o_tau_end[MAX_BEAM];
   __shared__ int o_rs[MAX_BEAM], o_re[MAX_BEAM], o_last[MAX_BEAM], o_ws[MAX_BEAM], o_we[MAX_BEAM], o_ref[MAX_BEAM];
@@ -328,28 +365,31 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
       key = r < nj ? ((k & ~1023ull) | (unsigned long long)(1023 - i)) : (unsigned long long)(1023 - i) >> 1;
     }
     s_key[i] = key;
+    s_ck[i] = 0ull;
   }
   if (tid < MAX_BEAM) s_sel[tid] = -1;
+  if (tid < 2) s_cnt[tid] = 0;
+  if (tid == 2) s_min = ~0ull;
   lds_barrier();
   TRACE_POINT(p, u, 9);
   int ne = 0;
 #pragma unroll 8
   for (int j = 0; j < Wb; ++j) ne += o_n[j];
-  // ---- rank: L lanes per entry, each comparing against every L-th quad of keys ----------------
+  // ---- rank the contenders: L lanes per entry, each comparing against every L-th quad of keys ----
   {
-    const int L = NE <= BLOCK / 8 ? 8 : (NE <= BLOCK / 4 ? 4 : (NE <= BLOCK / 2 ? 2 : 1));
+    const int NC = pack_contenders<BLOCK>(s_key, NE, Wb, o_n, s_ck, s_cidx, s_cnt, &s_min);
+    const int L = NC <= BLOCK / 8 ? 8 : (NC <= BLOCK / 4 ? 4 : (NC <= BLOCK / 2 ? 2 : 1));
     const int part = tid & (L - 1);
-    const int quads = (NE + 3) >> 2;                       // (the padding holds zeros)
-    const ulonglong2* s_k2 = (const ulonglong2*)s_key;
-    for (int e0 = 0; e0 < NE; e0 += BLOCK / L) {
+    const int quads = (NC + 3) >> 2;                       // (zeros follow the packed keys)
+    const ulonglong2* s_k2 = (const ulonglong2*)s_ck;
+    for (int e0 = 0; e0 < NC; e0 += BLOCK / L) {
       const int e = e0 + tid / L;
-      const unsigned long long me = s_key[min(e, NE)];
-      const int rank0 = count_greater(s_k2, me, part, L, quads);
-      int rank = rank0;
+      const unsigned long long me = s_ck[min(e, NC)];
+      int rank = count_greater(s_k2, me, part, L, quads);
       if (L >= 2) rank += dpp_i<0xB1, 0xf>(0, rank);       // quad_perm [1,0,3,2]
       if (L >= 4) rank += dpp_i<0x4E, 0xf>(0, rank);       // quad_perm [2,3,0,1]
       if (L == 8) rank += dpp_i<0x104, 0xf>(0, rank);      // row_shl:4: the first lane of the eight gets the other quad's sum
-      if (part == 0 && e < NE && me > 1023ull && rank < Wb) s_sel[rank] = e;
+      if (part == 0 && e < NC && rank < Wb) s_sel[rank] = s_cidx[e];
     }
   }
   lds_barrier();
@@ -510,6 +550,8 @@ __global__ __launch_bounds__(BLOCK) void k_select_split(Params p, int l, int cur
 #pragma unroll 8
   for (int j = 0; j < Wb; ++j) ne += o_n[j];
   const int n_new = min(ne, Wb);
+  // (all entries against all: packing the contenders first, as the per-utterance kernel does, costs two
+  // barriers more than it saves at these sizes -- measured)
   {
     const int L = NE <= 64 ? 4 : (NE <= 128 ? 2 : 1);
     const int part = tid & (L - 1);
@@ -518,8 +560,7 @@ __global__ __launch_bounds__(BLOCK) void k_select_split(Params p, int l, int cur
     for (int e0 = 0; e0 < NE; e0 += BLOCK / L) {
       const int e = e0 + tid / L;
       const unsigned long long me = s_key[min(e, NE)];
-      const int rank0 = count_greater(s_k2, me, part, L, quads);
-      int rank = rank0;
+      int rank = count_greater(s_k2, me, part, L, quads);
       if (L >= 2) rank += dpp_i<0xB1, 0xf>(0, rank);       // quad_perm [1,0,3,2]
       if (L == 4) rank += dpp_i<0x4E, 0xf>(0, rank);       // quad_perm [2,3,0,1]
       if (part == 0 && e < NE && me > 1023ull) {
