@@ -39,7 +39,8 @@ enum {
   CTCBS_EINVAL = -1,  /* bad argument or unsupported size (see limits below)             */
   CTCBS_ENOMEM = -2,  /* device or host allocation failed                                */
   CTCBS_EHIP = -3,    /* a HIP runtime call failed; ctcbs_last_hip_error() has the code  */
-  CTCBS_ESTATE = -4,  /* call not valid in the handle's state                            */
+  CTCBS_ESTATE = -4,  /* call not valid in the handle's state, or (ctcbs_finalize) a kernel's
+                         own consistency check failed during the decode: no result          */
   CTCBS_ECAP = -5     /* caller's output capacity too small                              */
 };
 

@@ -112,6 +112,7 @@ struct Params {
   unsigned long long* cells; // [U] prefix-score terms so far
   unsigned long long* groups;// [U] live (utterance, beam) groups so far
   int32_t* n_finished;       // [1]
+  int32_t* err;              // [1] bits set by the kernels' own consistency checks (0: none failed)
   int32_t* union_win;        // [2][2] per step parity: (min tau, max of min(tau~ + M2, T)) over live hypotheses
   int32_t* host_finished;    // [1] host-resident copy (device-mapped pinned memory), one step behind
   // back-pointer trie, level l holds the hypotheses of length l: [l_cap+1][U][Wb]
@@ -144,6 +145,15 @@ __device__ __forceinline__ float lae(float a, float b) {
 // global memory to other waves of the block.
 __device__ __forceinline__ void lds_barrier() {
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Consistency checks on indices that come from device data (candidate ids, list entries, time
+// indices): a value outside its range is clamped into it, so that no access leaves its array, and
+// the step's error bit is set; ctcbs_finalize then reports CTCBS_ESTATE instead of a result.
+enum { ERR_CAND_ID = 1, ERR_WINDOW = 2, ERR_LIST_ENTRY = 4, ERR_TOKEN = 8, ERR_TIME_INDEX = 16, ERR_BACKTRACK = 32 };
+__device__ __forceinline__ int checked(const Params& p, int v, int lo, int hi, int bit) {
+  if (v < lo || v > hi) { atomicOr(p.err, bit); v = v < lo ? lo : hi; }
+  return v;
 }
 
 __device__ __forceinline__ float canon0(float v) { return v < LOG0_CLASS ? LOG0F : v; }

@@ -157,6 +157,7 @@ static int ingest(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens) {
   }
   HIPCHK(hipMemsetAsync(p.grp_n, 0, sizeof(int32_t) * UW, st));
   HIPCHK(hipMemsetAsync(p.stopped, 0, sizeof(int32_t) * UW, st));
+  HIPCHK(hipMemsetAsync(p.err, 0, sizeof(int32_t), st));
   {
     const int nvt = (p.V + 255) / 256, ntt = (c.t_max + 5 + 31) / 32;   // stored indices 0 .. t_max + 4
     const int n_tiles = nvt * ntt, per_xcd = (n_tiles + 7) / 8;
@@ -220,7 +221,7 @@ static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens)
   A(p.grp_inc, UW * Wb); A(p.grp_att, UW * Wb);
   A(p.ctc_eos, UW); A(p.joint_eos, UW); A(p.stopped, UW); A(p.grp_cells, UW);
   A(p.utt, (size_t)U); A(p.finished, (size_t)((U + 3) & ~3));   /* read as whole words by the score kernel */ A(p.cells, (size_t)U); A(p.groups, (size_t)U);
-  A(p.n_finished, (size_t)1); A(p.union_win, (size_t)4);
+  A(p.n_finished, (size_t)1); A(p.union_win, (size_t)4); A(p.err, (size_t)1);
   const size_t trie_n = (size_t)(h->l_cap_alloc + 1) * UW;
   A(p.trie_parent, trie_n); A(p.trie_token, trie_n); A(p.trie_tau, trie_n);
   A(p.out_parent, UW); A(p.out_token, UW); A(p.out_score, UW); A(p.out_live, UW);
@@ -436,7 +437,10 @@ extern "C" int ctcbs_finalize(ctcbs_t* h, int32_t* h_tokens, int32_t cap, int32_
   HIPCHK(hipMemcpyAsync(nt.data(), h->d_ntok, (size_t)U * 4, hipMemcpyDeviceToHost, h->stream));
   HIPCHK(hipMemcpyAsync(fl.data(), h->d_flags, (size_t)U * 4, hipMemcpyDeviceToHost, h->stream));
   HIPCHK(hipMemcpyAsync(h_score, h->d_score, (size_t)U * 4, hipMemcpyDeviceToHost, h->stream));
+  int32_t err = 0;
+  HIPCHK(hipMemcpyAsync(&err, h->p.err, sizeof err, hipMemcpyDeviceToHost, h->stream));
   HIPCHK(hipStreamSynchronize(h->stream));
+  if (err != 0) return CTCBS_ESTATE;     // a kernel's consistency check failed during this decode: no result
   for (int u = 0; u < U; ++u) {
     if (nt[u] < 0 || nt[u] > cap) return CTCBS_ECAP;
     h_ntok[u] = nt[u];

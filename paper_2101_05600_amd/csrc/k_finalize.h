@@ -18,7 +18,7 @@ __global__ __launch_bounds__(BLOCK) void k_finalize(Params p, int cur, int steps
     int level, slot, flag = 0;
     double sc;
     if (st.n_ended > 0) {
-      level = st.best_step - 1; slot = st.best_slot; sc = st.best_score;
+      level = checked(p, st.best_step - 1, 0, steps_done, ERR_BACKTRACK); slot = st.best_slot; sc = st.best_score;
     } else {
       flag = 1;
       // beam of the last step this utterance took part in; slot 0 is its best hypothesis
@@ -44,7 +44,10 @@ __global__ __launch_bounds__(BLOCK) void k_finalize(Params p, int cur, int steps
     __syncthreads();
     if (tid == 0) {
       int slot = s_slot0;
-      for (int k = level; k >= 1; --k) { s_path[k] = (unsigned char)slot; slot = s_par[k * Wb + slot]; }
+      for (int k = level; k >= 1; --k) {
+        if (slot >= Wb) { atomicOr(p.err, ERR_BACKTRACK); slot = 0; }   // (a dead slot on the path: -1 read back as 255)
+        s_path[k] = (unsigned char)slot; slot = s_par[k * Wb + slot];
+      }
     }
     __syncthreads();
     for (int k = 1 + tid; k <= level; k += BLOCK) {
@@ -55,6 +58,7 @@ __global__ __launch_bounds__(BLOCK) void k_finalize(Params p, int cur, int steps
   } else if (tid == 0) {
     int slot = s_slot0;
     for (int k = level; k >= 1; --k) {
+      slot = checked(p, slot, 0, Wb - 1, ERR_BACKTRACK);
       const size_t idx = ((size_t)k * p.U + u) * Wb + slot;
       tokens[(size_t)u * cap + k - 1] = p.trie_token[idx];
       frames[(size_t)u * cap + k - 1] = p.trie_tau[idx];

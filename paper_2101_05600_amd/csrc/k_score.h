@@ -337,7 +337,7 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p
   float* s_inc = (float*)(smem + sm.off_small) + 3 * Ks;    // after J (2 words each) and cand_id
   float* s_av = s_inc + Ks;
   float* s_pre = s_av + Ks;                                // eos-run rule: prefix score without the last R frames
-  double* s_Jraw = (double*)(s_pre + Ks + (Ks & 1));       // joint score as computed (NaN kept), for the global copy
+  double* s_Jraw = (double*)(s_pre + Ks);                  // joint score as computed (NaN kept), for the global copy (6 Ks floats in: 8-byte aligned)
   int32_t* g_cid = p.cand_id + (size_t)grp * K;
 
   // logits mode: the row holds unnormalised scores; log_softmax is folded in here (the order of
@@ -376,6 +376,8 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p
     if (p.win_m1 >= 0) s = max(s, tau - p.win_m1);
     if (p.win_m2 >= 0) e = min(e, tau_end + p.win_m2);
   }
+  s = checked(p, s, 1, T + 1, ERR_WINDOW);                 // (an empty window is e < s; its loads stay inside the row)
+  e = checked(p, e, -1, T, ERR_WINDOW);
   const int W = e >= s ? e - s + 1 : 0;
   const int t0 = s & ~3;                                   // column loads start on a 16-byte boundary
   const int n4 = W > 0 ? ((e - t0) >> 2) + 1 : 0;
@@ -385,7 +387,7 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p
   // Stored forward variables have the per-frame reference B_t taken out (see Params::Bcum); all
   // increments of this step are relative to off'(g) + B_r, r = g's reference frame
   const double* Bu = p.Bcum + (size_t)u * p.Tp;
-  const double Bref = Bu[ref];
+  const double Bref = Bu[checked(p, ref, 0, T, ERR_TIME_INDEX)];
   const double offr = off + Bref;
 
   // eos inputs (thread 0), fetched now so that the epilogue does not wait for them
@@ -468,7 +470,7 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p
 #pragma unroll
     for (int b = 0; b < CB; ++b) {
       const int c = c0 + b * NSG;
-      ids[b] = (c < K) ? (smallk ? s_cid[c] : g_cid[c]) : -1;
+      ids[b] = (c < K) ? checked(p, smallk ? s_cid[c] : g_cid[c], 0, V - 1, ERR_CAND_ID) : -1;
       const float4* col = (const float4*)(xu + (size_t)(ids[b] < 0 ? 0 : ids[b]) * p.Tp + t0);
 #pragma unroll
       for (int it = 0; it < IT; ++it)                        // unconditional (clamped) loads: all in flight together

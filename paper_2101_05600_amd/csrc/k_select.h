@@ -76,6 +76,7 @@ __device__ __forceinline__ ArgMax wave_argmax(ArgMax x) {
 struct SurvivorIn {
   int par, tok, s, en, rs, re, ptau, ptau_end, plast, pref;
   float inc;
+  int T;            // frames of the utterance (bounds of every time index)
 };
 // FPL consecutive frames per lane, 64 * FPL frames per pass.
 template <int FPL>
@@ -83,18 +84,19 @@ __device__ __forceinline__ void wave_survivor_fpl(const Params& p, int u, int n,
                                                   int& arg_n, int& arg_b, float& delta_out) {
   const int lane = threadIdx.x & 63;
   const size_t h0 = (size_t)u * p.Wb;
-  const size_t hp = h0 + in.par;
+  const size_t hp = h0 + checked(p, in.par, 0, p.Wb - 1, ERR_LIST_ENTRY);
   const float* xu = p.xT + (size_t)u * p.V * p.Tp;
   const float* x0 = xu + (size_t)p.blank_id * p.Tp;
-  const float* xc = xu + (size_t)in.tok * p.Tp;
+  const float* xc = xu + (size_t)checked(p, in.tok, 0, p.V - 1, ERR_TOKEN) * p.Tp;
   const double* Bu = p.Bcum + (size_t)u * p.Tp;
   const float* pgn = p.gn[cur] + hp * p.Tp;
   const float* pgb = p.gb[cur] + hp * p.Tp;
   float* cgn = p.gn[cur ^ 1] + (h0 + n) * p.Tp;
   float* cgb = p.gb[cur ^ 1] + (h0 + n) * p.Tp;
-  const int s = in.s, en = in.en, rs = in.rs, re = in.re;
-  const double Bnew = Bu[in.ptau];                       // the child's reference frame is the parent's tau
-  const float delta = in.inc + (float)(Bu[in.pref] - Bnew);
+  const int T = in.T;
+  const int s = checked(p, in.s, 1, T, ERR_WINDOW), en = checked(p, in.en, s, T, ERR_WINDOW), rs = in.rs, re = in.re;
+  const double Bnew = Bu[checked(p, in.ptau, 0, T, ERR_TIME_INDEX)];   // the child's reference frame is the parent's tau
+  const float delta = in.inc + (float)(Bu[checked(p, in.pref, 0, T, ERR_TIME_INDEX)] - Bnew);
   delta_out = delta;
   const bool rep = (in.tok == in.plast);
   const int lo = max(s, in.ptau);
@@ -399,7 +401,7 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
   const int n_new = min(ne, Wb);
   if (w == 0) {
     const bool has_best = ne > 0;
-    const double best = has_best ? s_J[s_sel[0]] : LOG0D;
+    const double best = has_best ? s_J[checked(p, s_sel[0], 0, NE - 1, ERR_LIST_ENTRY)] : LOG0D;
     const int j = lane < Wb ? lane : 0;
     const bool mine = lane < Wb && o_live[j];
     const bool fin = wave_ended_set(p, u, l, T, lmax_u, has_best, best, n_new, mine, o_je[j], o_stp[j], o_tau[j],
@@ -414,9 +416,9 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
   // finished utterance's new state is computed too but never used: its slots are marked dead.)
   const size_t trie_l = ((size_t)l * p.U + u) * Wb;
   for (int n = w - 1; n >= 0 && n < n_new; n += NW - 1) {
-    const int e = s_sel[n], par = s_par[e];
+    const int e = checked(p, s_sel[n], 0, NE - 1, ERR_LIST_ENTRY), par = s_par[e];
     SurvivorIn in;
-    in.par = par; in.tok = s_tok[e]; in.inc = s_inc[e];
+    in.par = par; in.tok = s_tok[e]; in.inc = s_inc[e]; in.T = T;
     in.s = o_ws[par]; in.en = o_we[par]; in.rs = o_rs[par]; in.re = o_re[par];
     in.ptau = o_tau[par]; in.ptau_end = o_tau_end[par]; in.plast = o_last[par]; in.pref = o_ref[par];
     int arg_n, arg_b;
@@ -435,7 +437,7 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
   for (int n = tid; n < Wb; n += BLOCK) {
     const size_t h = h0 + n;
     if (n < n_new) {
-      const int e = s_sel[n], par = s_par[e], tok = s_tok[e];
+      const int e = checked(p, s_sel[n], 0, NE - 1, ERR_LIST_ENTRY), par = s_par[e], tok = s_tok[e];
       p.out_parent[h] = par; p.out_token[h] = tok; p.out_score[h] = (float)s_J[e];
       p.out_live[h] = fin ? 0 : 1;
       p.trie_parent[trie_l + n] = par; p.trie_token[trie_l + n] = tok;
@@ -577,9 +579,9 @@ __global__ __launch_bounds__(BLOCK) void k_select_split(Params p, int l, int cur
     // ---- new hypothesis n: forward variables, record, outputs, back-pointer -----------------
     const size_t h = h0 + n;
     if (n < n_new) {
-      const int e = s_pick[0], par = e / Wb;
+      const int e = checked(p, s_pick[0], 0, NE - 1, ERR_LIST_ENTRY), par = e / Wb;
       SurvivorIn in;
-      in.par = par; in.tok = s_tok[e]; in.inc = s_inc[e];
+      in.par = par; in.tok = s_tok[e]; in.inc = s_inc[e]; in.T = T;
       in.s = o_ws[par]; in.en = o_we[par]; in.rs = o_rs[par]; in.re = o_re[par];
       in.ptau = o_tau[par]; in.ptau_end = o_tau_end[par]; in.plast = o_last[par]; in.pref = o_ref[par];
       int arg_n, arg_b;
@@ -606,7 +608,7 @@ __global__ __launch_bounds__(BLOCK) void k_select_split(Params p, int l, int cur
   } else if (lead && w == 1) {
     // ---- the utterance as a whole: ended set, end detection, live flags ----------------------
     const bool has_best = ne > 0;
-    const double best = has_best ? s_J[s_pick[1]] : LOG0D;
+    const double best = has_best ? s_J[checked(p, s_pick[1], 0, NE - 1, ERR_LIST_ENTRY)] : LOG0D;
     const int j = lane < Wb ? lane : 0;
     const bool mine = lane < Wb && o_live[j];
     const bool fin = wave_ended_set(p, u, l, T, lmax_u, has_best, best, n_new, mine, o_je[j], o_stp[j], o_tau[j],
