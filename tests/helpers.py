@@ -87,14 +87,50 @@ class GpuDecoder:
             self.h = None
 
 
+class EmuDecoder(GpuDecoder):
+    """The same driver over the CPU build of the kernels (tests/cpu_emu): "device" memory is host
+    memory, so plain numpy arrays stand where GpuDecoder has CUDA tensors.  The caller must have
+    pointed the binding at the CPU library before its first use (see tests/test_cpu_emulation.py)."""
+
+    def __init__(self, w, ctc, lens, poll_every=0):
+        import paper_2101_05600_amd as m
+        self.m, self.w = m, w
+        self.U, self.Wb, self.V = len(lens), w["beam"], w["vocab"]
+        self.lens = np.asarray(lens, np.int32)
+        self.cfg = m.make_config(n_utt=self.U, t_max=ctc.shape[1], poll_every=poll_every,
+                                 **{k: v for k, v in w.items() if k not in ("n_utt",)})
+        d_ctc = np.ascontiguousarray(ctc, dtype=np.float32)
+        self.h = m.ctcbs_create(self.cfg, d_ctc.ctypes.data, self.lens)
+        self.out = m.StepOut()
+        self.d_att = np.empty((self.U, self.Wb, self.V), dtype=np.float32)
+        self.K = int(m.ctcbs_peek(self.h, m.PEEK_N_CAND)[0])
+
+    def step(self, att):
+        self.d_att[...] = att
+        return self.m.ctcbs_step(self.h, self.d_att.ctypes.data, self.out)
+
+    def outputs(self):
+        o, U, Wb = self.out, self.U, self.Wb
+
+        def g(p, shape, dt):
+            n = int(np.prod(shape)) * np.dtype(dt).itemsize
+            return np.frombuffer((ctypes.c_char * n).from_address(int(p)), dtype=dt).reshape(shape).copy()
+        return dict(parent=g(o.d_parent, (U, Wb), np.int32), token=g(o.d_token, (U, Wb), np.int32),
+                    score=g(o.d_score, (U, Wb), np.float32), live=g(o.d_live, (U, Wb), np.uint8),
+                    finished=g(o.d_finished, (U,), np.uint8), tau=g(o.d_tau, (U, Wb), np.int32),
+                    tau_end=g(o.d_tau_end, (U, Wb), np.int32),
+                    eos_added=g(o.d_eos_added, (U, Wb), np.uint8),
+                    stopped=g(o.d_stopped, (U, Wb), np.uint8))
+
+
 def lockstep_decode(w, ctc, lens, peek=True, check_utts=None, max_steps=None, progress=None,
-                    att_fn=None, gpu_att_fn=None, eps=1e-4):
+                    att_fn=None, gpu_att_fn=None, eps=1e-4, decoder_cls=None):
     """Decode the batch on the GPU with host-generated attention rows, validating every step of
     the utterances in check_utts (default: all) against the oracle.  Returns (report, results)."""
     U, Wb = len(lens), w["beam"]
     check = list(range(U)) if check_utts is None else list(check_utts)
     ls = Lockstep([ctc[u, :lens[u]] for u in check], orc_cfg_from(w), eps=eps, utt_ids=check)
-    dec = GpuDecoder(w, ctc, lens)
+    dec = (decoder_cls or GpuDecoder)(w, ctc, lens)
     try:
         basis = gen.prefix_hash([])
         hashes = [[basis] * Wb for _ in range(U)]

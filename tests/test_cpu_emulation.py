@@ -1,0 +1,92 @@
+"""The kernel SOURCES, run on the CPU under sanitizers (no GPU needed).
+
+tests/cpu_emu builds the library's HIP files with g++ against a stand-in for the HIP runtime header:
+work-groups run one after the other with one OS thread per work-item, barriers, 64-lane wave
+operations (shuffles, ballots, DPP, readlane) and LDS emulated, "device memory" on the heap.  Small
+batches are then decoded through the ordinary C ABI and compared with the oracle step by step, just
+as the GPU tests do.  What this adds to them: AddressSanitizer and UBSan see every access the kernels
+make (an index that leaves its array is an error here, not a fault on a shared machine),
+ThreadSanitizer sees a missing barrier as a data race, and LDS starts out filled with a poison
+pattern, so a kernel that reads what it has not written does not get zeros.  It says nothing about
+speed and does not replace the GPU tests (the real wave execution, memory model and intrinsics are
+only there)."""
+import os
+import subprocess
+import sys
+
+import pytest
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+sys.path.insert(0, os.path.join(HERE, "cpu_emu"))
+
+import build_emu  # noqa: E402
+
+
+def _runtime(name):
+    path = subprocess.run(["gcc", f"-print-file-name={name}"], capture_output=True, text=True).stdout.strip()
+    return path if os.path.isabs(path) and os.path.exists(path) else None
+
+
+def _run(so, preload, env_extra, cases, timeout=900):
+    env = dict(os.environ)
+    env["LD_PRELOAD"] = preload + (":" + env["LD_PRELOAD"] if env.get("LD_PRELOAD") else "")
+    env.update(env_extra)
+    env["OMP_NUM_THREADS"] = "1"
+    r = subprocess.run([sys.executable, os.path.join(HERE, "cpu_emu", "run_case.py"), so, *cases],
+                       capture_output=True, text=True, env=env, timeout=timeout)
+    return r
+
+
+@pytest.fixture(scope="module")
+def build_dir(tmp_path_factory):
+    return str(tmp_path_factory.mktemp("cpu_emu"))
+
+
+def test_kernels_under_address_and_ub_sanitizers(build_dir):
+    asan = _runtime("libasan.so")
+    if asan is None:
+        pytest.skip("no AddressSanitizer runtime in this toolchain")
+    so = build_emu.build(os.path.join(build_dir, "asan"), sanitize=True)
+    r = _run(so, asan, {"ASAN_OPTIONS": "detect_leaks=0:halt_on_error=1:verify_asan_link_order=0",
+                        "UBSAN_OPTIONS": "halt_on_error=1:print_stacktrace=1"},
+             ["windowed", "batch_window", "all_candidates", "logits_odd_vocab"])
+    out = r.stdout + r.stderr
+    if r.returncode != 0 and "emu ok" not in out and ("Shadow memory" in out or "ASan runtime does not come first" in out):
+        pytest.skip("AddressSanitizer cannot start under this process environment")
+    assert r.returncode == 0, out[-4000:]
+    assert "ERROR: AddressSanitizer" not in out and "runtime error:" not in out, out[-4000:]
+    assert out.count("emu ok") == 4, out[-2000:]
+
+
+def test_kernels_under_thread_sanitizer(build_dir):
+    tsan = _runtime("libtsan.so")
+    if tsan is None:
+        pytest.skip("no ThreadSanitizer runtime in this toolchain")
+    so = build_emu.build(os.path.join(build_dir, "tsan"), sanitize="thread")
+    r = _run(so, tsan, {"TSAN_OPTIONS": "halt_on_error=0:report_signal_unsafe=0:history_size=2"},
+             ["windowed", "batch_window"])
+    out = r.stdout + r.stderr
+    if r.returncode != 0 and "emu ok" not in out and "ThreadSanitizer: unexpected memory mapping" in out:
+        pytest.skip("ThreadSanitizer cannot start under this process environment")
+    assert r.returncode == 0, out[-4000:]
+    assert "WARNING: ThreadSanitizer" not in out, out[-6000:]
+    assert out.count("emu ok") == 2, out[-2000:]
+
+
+def test_thread_sanitizer_run_notices_a_missing_barrier(build_dir):
+    """Self-test of the method: with the barrier between building the list keys and ranking them
+    taken out of the (copied) split select kernel, the same run reports data races."""
+    tsan = _runtime("libtsan.so")
+    if tsan is None:
+        pytest.skip("no ThreadSanitizer runtime in this toolchain")
+    plant = ("k_select.h",
+             "  if (fs != 0 && fs < l) return;           // outputs of a finished utterance were settled when it finished\n"
+             "  lds_barrier();",
+             "  if (fs != 0 && fs < l) return;\n  /* planted mistake: no barrier here */")
+    so = build_emu.build(os.path.join(build_dir, "tsan_planted"), sanitize="thread", plant=plant)
+    r = _run(so, tsan, {"TSAN_OPTIONS": "halt_on_error=0:report_signal_unsafe=0:history_size=2"}, ["windowed"], timeout=600)
+    out = r.stdout + r.stderr
+    if "emu ok" not in out and "ThreadSanitizer: unexpected memory mapping" in out:
+        pytest.skip("ThreadSanitizer cannot start under this process environment")
+    assert "WARNING: ThreadSanitizer: data race" in out and "k_select_split" in out, out[-3000:]
