@@ -116,7 +116,11 @@ __global__ __launch_bounds__(64) void k_init_state(Params p, int n_empty) {
     p.h_live[0][h] = (j == 0 && T > 0); p.h_last[0][h] = -1;
     p.h_rs[0][h] = 0; p.h_re[0][h] = T; p.h_tau[0][h] = 0; p.h_tau_end[0][h] = 0; p.h_ref[0][h] = 0;
     p.h_off[0][h] = 0.0; p.h_att[0][h] = 0.0; p.h_joint[0][h] = 0.0;
-    p.h_live[1][h] = 0;
+    // the other buffer: dead until the first selection fills it, but never left holding what the
+    // allocation happened to contain (a kernel may load a dead slot's record before it looks at its flag)
+    p.h_live[1][h] = 0; p.h_last[1][h] = -1;
+    p.h_rs[1][h] = 0; p.h_re[1][h] = T; p.h_tau[1][h] = 0; p.h_tau_end[1][h] = 0; p.h_ref[1][h] = 0;
+    p.h_off[1][h] = 0.0; p.h_att[1][h] = 0.0; p.h_joint[1][h] = 0.0;
     p.out_live[h] = (j == 0 && T > 0); p.out_parent[h] = 0; p.out_token[h] = -1; p.out_score[h] = 0.0f;
     p.out_tau[h] = 0; p.out_tau_end[h] = 0; p.out_eos_added[h] = 0; p.out_stopped[h] = 0;
     p.trie_parent[h] = 0; p.trie_token[h] = -1; p.trie_tau[h] = 0;   // level 0: the empty hypothesis

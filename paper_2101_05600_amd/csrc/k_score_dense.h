@@ -50,7 +50,8 @@ __global__ __launch_bounds__(BLOCK) void k_score_dense(Params p, const float* __
     int s = l > 1 ? l : 1, e = T;
     if (p.win_m1 >= 0) s = max(s, tau - p.win_m1);
     if (p.win_m2 >= 0) e = min(e, tau_end + p.win_m2);
-    const int ref = p.h_ref[cur][h];
+    // (a slot that never held a hypothesis has a record nobody wrote: nothing of it may steer an access)
+    const int ref = live ? checked(p, p.h_ref[cur][h], 0, T, ERR_TIME_INDEX) : 0;
     q_live[tid] = live; q_last[tid] = p.h_last[cur][h]; q_s[tid] = s; q_e[tid] = e;
     q_rs[tid] = p.h_rs[cur][h]; q_re[tid] = p.h_re[cur][h]; q_ref[tid] = ref;
     q_offr[tid] = p.h_off[cur][h] + Bu[ref];

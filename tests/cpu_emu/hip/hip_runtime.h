@@ -45,7 +45,13 @@ typedef void* hipStream_t;
 typedef void* hipEvent_t;
 enum hipMemcpyKind { hipMemcpyHostToDevice = 1, hipMemcpyDeviceToHost = 2, hipMemcpyDeviceToDevice = 3 };
 enum { hipEventDisableTiming = 2, hipHostMallocMapped = 2, hipFuncAttributeMaxDynamicSharedMemorySize = 8 };
-inline hipError_t hipMalloc(void** p, size_t n) { *p = malloc(n ? n : 1); return *p ? hipSuccess : hipErrorOutOfMemory; }
+// device memory comes back holding garbage (0xBE bytes: indices far out of range, floats near -0.37):
+// whatever a kernel reads before it was written must not be able to steer an access
+inline hipError_t hipMalloc(void** p, size_t n) {
+  *p = malloc(n ? n : 1);
+  if (*p) memset(*p, 0xBE, n ? n : 1);
+  return *p ? hipSuccess : hipErrorOutOfMemory;
+}
 template <class T> inline hipError_t hipMalloc(T** p, size_t n) { return hipMalloc((void**)p, n); }
 inline hipError_t hipFree(void* p) { free(p); return hipSuccess; }
 inline hipError_t hipHostMalloc(void** p, size_t n, unsigned = 0) { return hipMalloc(p, n); }

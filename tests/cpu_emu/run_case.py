@@ -29,6 +29,9 @@ CASES = {
     # every id a candidate: all-candidates score kernel, list builder from registers
     "all_candidates": (dict(n_utt=1, vocab=12, beam=2, cand_k=0, win_m1=-1, win_m2=-1, end_flags=3,
                             max_len_ratio=0.4), [15]),
+    # fewer ids than beam slots: most slots never hold a hypothesis, their records are never written
+    "all_candidates_few_ids": (dict(n_utt=2, vocab=6, beam=6, cand_k=0, win_m1=-1, win_m2=-1, end_flags=3,
+                                    max_len_ratio=0.4), [13, 9]),
     # logits in, odd vocabulary (radix selection), one candidate per hypothesis
     "logits_odd_vocab": (dict(n_utt=1, vocab=33, beam=2, cand_k=1, win_m1=3, win_m2=8, end_flags=2, att_is_logits=1,
                               max_len_ratio=0.4), [19]),
