@@ -39,6 +39,25 @@ def _run(so, preload, env_extra, cases, timeout=900):
     return r
 
 
+def _preload_works(preload, env_extra):
+    """Can a Python child start at all with this sanitizer runtime preloaded (it cannot in every
+    environment: another preloaded library first, an unusual memory layout)?"""
+    env = dict(os.environ)
+    env["LD_PRELOAD"] = preload + (":" + env["LD_PRELOAD"] if env.get("LD_PRELOAD") else "")
+    env.update(env_extra)
+    try:
+        r = subprocess.run([sys.executable, "-c", "import ctypes, numpy; print('probe ok')"],
+                           capture_output=True, text=True, env=env, timeout=120)
+    except subprocess.TimeoutExpired:
+        return False
+    return r.returncode == 0 and "probe ok" in r.stdout
+
+
+ASAN_ENV = {"ASAN_OPTIONS": "detect_leaks=0:halt_on_error=1:verify_asan_link_order=0",
+            "UBSAN_OPTIONS": "halt_on_error=1:print_stacktrace=1"}
+TSAN_ENV = {"TSAN_OPTIONS": "halt_on_error=0:report_signal_unsafe=0:history_size=2"}
+
+
 @pytest.fixture(scope="module")
 def build_dir(tmp_path_factory):
     return str(tmp_path_factory.mktemp("cpu_emu"))
@@ -48,13 +67,12 @@ def test_kernels_under_address_and_ub_sanitizers(build_dir):
     asan = _runtime("libasan.so")
     if asan is None:
         pytest.skip("no AddressSanitizer runtime in this toolchain")
+    if not _preload_works(asan, ASAN_ENV):
+        pytest.skip("a Python child does not start with the AddressSanitizer runtime preloaded here")
     so = build_emu.build(os.path.join(build_dir, "asan"), sanitize=True)
-    r = _run(so, asan, {"ASAN_OPTIONS": "detect_leaks=0:halt_on_error=1:verify_asan_link_order=0",
-                        "UBSAN_OPTIONS": "halt_on_error=1:print_stacktrace=1"},
+    r = _run(so, asan, ASAN_ENV,
              ["windowed", "batch_window", "all_candidates", "all_candidates_few_ids", "logits_odd_vocab"])
     out = r.stdout + r.stderr
-    if r.returncode != 0 and "emu ok" not in out and ("Shadow memory" in out or "ASan runtime does not come first" in out):
-        pytest.skip("AddressSanitizer cannot start under this process environment")
     assert r.returncode == 0, out[-4000:]
     assert "ERROR: AddressSanitizer" not in out and "runtime error:" not in out, out[-4000:]
     assert out.count("emu ok") == 5, out[-2000:]
@@ -64,12 +82,11 @@ def test_kernels_under_thread_sanitizer(build_dir):
     tsan = _runtime("libtsan.so")
     if tsan is None:
         pytest.skip("no ThreadSanitizer runtime in this toolchain")
+    if not _preload_works(tsan, TSAN_ENV):
+        pytest.skip("a Python child does not start with the ThreadSanitizer runtime preloaded here")
     so = build_emu.build(os.path.join(build_dir, "tsan"), sanitize="thread")
-    r = _run(so, tsan, {"TSAN_OPTIONS": "halt_on_error=0:report_signal_unsafe=0:history_size=2"},
-             ["windowed", "batch_window"])
+    r = _run(so, tsan, TSAN_ENV, ["windowed", "batch_window"])
     out = r.stdout + r.stderr
-    if r.returncode != 0 and "emu ok" not in out and "ThreadSanitizer: unexpected memory mapping" in out:
-        pytest.skip("ThreadSanitizer cannot start under this process environment")
     assert r.returncode == 0, out[-4000:]
     assert "WARNING: ThreadSanitizer" not in out, out[-6000:]
     assert out.count("emu ok") == 2, out[-2000:]
@@ -85,9 +102,9 @@ def test_thread_sanitizer_run_notices_a_missing_barrier(build_dir):
              "  if (fs != 0 && fs < l) return;           // outputs of a finished utterance were settled when it finished\n"
              "  lds_barrier();",
              "  if (fs != 0 && fs < l) return;\n  /* planted mistake: no barrier here */")
+    if not _preload_works(tsan, TSAN_ENV):
+        pytest.skip("a Python child does not start with the ThreadSanitizer runtime preloaded here")
     so = build_emu.build(os.path.join(build_dir, "tsan_planted"), sanitize="thread", plant=plant)
-    r = _run(so, tsan, {"TSAN_OPTIONS": "halt_on_error=0:report_signal_unsafe=0:history_size=2"}, ["windowed"], timeout=600)
+    r = _run(so, tsan, TSAN_ENV, ["windowed"], timeout=600)
     out = r.stdout + r.stderr
-    if "emu ok" not in out and "ThreadSanitizer: unexpected memory mapping" in out:
-        pytest.skip("ThreadSanitizer cannot start under this process environment")
     assert "WARNING: ThreadSanitizer: data race" in out and "k_select_split" in out, out[-3000:]
