@@ -38,8 +38,53 @@ CASES = {
 }
 
 
+def executor_case():
+    """The job queue on two handles driven by two host threads (ctcbs_run_queue with the replay provider):
+    three small batches, each first decoded alone against the oracle; the queue must return the same.
+    Under ThreadSanitizer this is the check of the executor's own host code."""
+    ws, data, singles, recs = [], [], [], []
+    for j, lens in enumerate([[14, 9], [11, 0], [8, 13]]):
+        w = gen.workload("cfg1")
+        w.update(n_utt=2, vocab=24, beam=2, cand_k=4, win_m1=4, win_m2=4, end_flags=7, eos_run=2,
+                 max_len_ratio=0.4, seed=500 + j)
+        w["eos_id"] = w["vocab"] - 1
+        lens = np.asarray(lens, np.int32)
+        g = gen.workload_ctc(w, np.maximum(lens, 1))
+        ctc = np.full((2, 14, 24), np.nan, np.float32)
+        for u in range(2):
+            ctc[u, :lens[u]] = g[u, :lens[u]]
+        rows = []
+        rep, res = lockstep_decode(w, ctc, lens, check_utts=[u for u in range(2) if lens[u] > 0],
+                                   decoder_cls=EmuDecoder, gpu_att_fn=lambda a, rows=rows: rows.append(a.copy()) or a)
+        assert rep["max_score_err"] < 1e-4, rep
+        ws.append(w); data.append((np.ascontiguousarray(ctc), lens)); singles.append(res); recs.append(rows)
+    decs = [EmuDecoder(ws[0], data[0][0], data[0][1], poll_every=2) for _ in range(2)]
+    got = [None] * 3
+    cap = max(r["tokens"].shape[1] for r in singles)
+
+    def job_fn(job, slot, h, phase):
+        if phase == m.JOB_LOAD:
+            m.ctcbs_reset(h, data[job][0].ctypes.data, data[job][1])
+        else:
+            got[job] = m.ctcbs_finalize(h, 2, cap)
+    keep = [[np.ascontiguousarray(r) for r in rows] for rows in recs]
+    m.ctcbs_run_queue([d.h for d in decs], 3, job_fn, replay=[[r.ctypes.data for r in rows] for rows in keep],
+                      n_threads=2)
+    for j in range(3):
+        tok, nt, sc, frm, fl = got[j]
+        c = singles[j]["tokens"].shape[1]
+        assert np.array_equal(tok[:, :c], singles[j]["tokens"]) and np.array_equal(nt, singles[j]["ntok"]), j
+        assert np.array_equal(sc, singles[j]["score"]), j
+    for d in decs:
+        d.close()
+    print("emu ok executor", flush=True)
+
+
 def main():
     names = sys.argv[2:] or list(CASES)
+    if "executor" in names:
+        names.remove("executor")
+        executor_case()
     for name in names:
         over, lens = CASES[name]
         w = gen.workload("cfg1")

@@ -85,11 +85,11 @@ def test_kernels_under_thread_sanitizer(build_dir):
     if not _preload_works(tsan, TSAN_ENV):
         pytest.skip("a Python child does not start with the ThreadSanitizer runtime preloaded here")
     so = build_emu.build(os.path.join(build_dir, "tsan"), sanitize="thread")
-    r = _run(so, tsan, TSAN_ENV, ["windowed", "batch_window"])
+    r = _run(so, tsan, TSAN_ENV, ["windowed", "batch_window", "executor"])   # executor: two host threads, two handles
     out = r.stdout + r.stderr
     assert r.returncode == 0, out[-4000:]
     assert "WARNING: ThreadSanitizer" not in out, out[-6000:]
-    assert out.count("emu ok") == 2, out[-2000:]
+    assert out.count("emu ok") == 3, out[-2000:]
 
 
 def test_thread_sanitizer_run_notices_a_missing_barrier(build_dir):
