@@ -16,7 +16,7 @@ from test_gpu_parity import small
 
 pytestmark = pytest.mark.gpu
 
-N_CASES = 45
+N_CASES = 60
 
 
 def case_params(case, seed0=1):
