@@ -45,11 +45,15 @@ typedef void* hipStream_t;
 typedef void* hipEvent_t;
 enum hipMemcpyKind { hipMemcpyHostToDevice = 1, hipMemcpyDeviceToHost = 2, hipMemcpyDeviceToDevice = 3 };
 enum { hipEventDisableTiming = 2, hipHostMallocMapped = 2, hipFuncAttributeMaxDynamicSharedMemorySize = 8 };
-// device memory comes back holding garbage (0xBE bytes: indices far out of range, floats near -0.37):
+// device memory comes back holding garbage (0xBE bytes, or EMU_POISON: indices far out of range, floats near -0.37):
 // whatever a kernel reads before it was written must not be able to steer an access
+inline int emu_poison_byte() {
+  static const int b = getenv("EMU_POISON") ? (int)strtol(getenv("EMU_POISON"), nullptr, 0) & 0xff : 0xBE;
+  return b;
+}
 inline hipError_t hipMalloc(void** p, size_t n) {
   *p = malloc(n ? n : 1);
-  if (*p) memset(*p, 0xBE, n ? n : 1);
+  if (*p) memset(*p, emu_poison_byte(), n ? n : 1);
   return *p ? hipSuccess : hipErrorOutOfMemory;
 }
 template <class T> inline hipError_t hipMalloc(T** p, size_t n) { return hipMalloc((void**)p, n); }
