@@ -16,7 +16,7 @@ from test_gpu_parity import small
 
 pytestmark = pytest.mark.gpu
 
-N_CASES = 60
+RUNS = [(1, 60), (2, 40)]          # (seed of the list, cases): every case ran on the CPU build first
 
 
 def case_params(case, seed0=1):
@@ -53,14 +53,15 @@ def case_params(case, seed0=1):
     return mode, w, lens
 
 
-def test_random_small_configurations_one_process():
+@pytest.mark.parametrize("seed0,n_cases", RUNS)
+def test_random_small_configurations_one_process(seed0, n_cases):
     bad = []
-    for case in range(N_CASES):
-        mode, w, lens = case_params(case)
+    for case in range(n_cases):
+        mode, w, lens = case_params(case, seed0)
         used = [u for u in range(len(lens)) if lens[u] > 0]
         if not used:
             continue
-        print(f"case {case}: {mode} U={len(lens)} beam={w['beam']} V={w['vocab']} K={w['cand_k']} "
+        print(f"case {seed0}/{case}: {mode} U={len(lens)} beam={w['beam']} V={w['vocab']} K={w['cand_k']} "
               f"M=({w['win_m1']},{w['win_m2']}) union={w.get('win_union', 0)} end={w['end_flags']} lens={list(lens)}",
               flush=True)
         ctc = gen.workload_ctc(w, np.maximum(lens, 1))
