@@ -22,19 +22,19 @@ from helpers import EmuDecoder, lockstep_decode  # noqa: E402
 CASES = {
     # split select kernel, 16-lane score kernel, eos-run rule, an unused slot
     "windowed": (dict(n_utt=3, vocab=40, beam=3, cand_k=6, win_m1=5, win_m2=5, end_flags=7, eos_run=2,
-                      max_len_ratio=0.4), [17, 0, 26]),
+                      max_len_ratio=0.4), [12, 0, 18]),
     # per-utterance select kernel (batch-wide window), 64-lane score kernel (no end margin)
     "batch_window": (dict(n_utt=2, vocab=36, beam=2, cand_k=5, win_m1=4, win_m2=-1, win_union=1, end_flags=3,
-                          max_len_ratio=0.4), [21, 14]),
+                          max_len_ratio=0.4), [15, 10]),
     # every id a candidate: all-candidates score kernel, list builder from registers
     "all_candidates": (dict(n_utt=1, vocab=12, beam=2, cand_k=0, win_m1=-1, win_m2=-1, end_flags=3,
-                            max_len_ratio=0.4), [15]),
+                            max_len_ratio=0.4), [11]),
     # fewer ids than beam slots: most slots never hold a hypothesis, their records are never written
     "all_candidates_few_ids": (dict(n_utt=2, vocab=6, beam=6, cand_k=0, win_m1=-1, win_m2=-1, end_flags=3,
-                                    max_len_ratio=0.4), [13, 9]),
+                                    max_len_ratio=0.4), [9, 7]),
     # logits in, odd vocabulary (radix selection), one candidate per hypothesis
     "logits_odd_vocab": (dict(n_utt=1, vocab=33, beam=2, cand_k=1, win_m1=3, win_m2=8, end_flags=2, att_is_logits=1,
-                              max_len_ratio=0.4), [19]),
+                              max_len_ratio=0.4), [13]),
 }
 
 

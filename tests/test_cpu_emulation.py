@@ -58,53 +58,64 @@ ASAN_ENV = {"ASAN_OPTIONS": "detect_leaks=0:halt_on_error=1:verify_asan_link_ord
 TSAN_ENV = {"TSAN_OPTIONS": "halt_on_error=0:report_signal_unsafe=0:history_size=2"}
 
 
+PLANT = ("k_select.h",
+         "  if (fs != 0 && fs < l) return;           // outputs of a finished utterance were settled when it finished\n"
+         "  lds_barrier();",
+         "  if (fs != 0 && fs < l) return;\n  /* planted mistake: no barrier here */")
+
+
 @pytest.fixture(scope="module")
-def build_dir(tmp_path_factory):
-    return str(tmp_path_factory.mktemp("cpu_emu"))
+def runs(tmp_path_factory):
+    """Builds the three instrumented libraries and runs their children, all side by side (a build takes
+    most of a minute, a run about a minute, mostly waiting at emulated barriers).
+    -> {name: CompletedProcess, or a string saying why it could not run}"""
+    from concurrent.futures import ThreadPoolExecutor
+    root = str(tmp_path_factory.mktemp("cpu_emu"))
+    asan, tsan = _runtime("libasan.so"), _runtime("libtsan.so")
+    plan = {
+        "asan": (asan, ASAN_ENV, dict(sanitize=True),
+                 ["windowed", "batch_window", "all_candidates", "all_candidates_few_ids", "logits_odd_vocab"]),
+        # executor: the job queue with two host threads on two handles
+        "tsan": (tsan, TSAN_ENV, dict(sanitize="thread"), ["windowed", "batch_window", "executor"]),
+        "tsan_planted": (tsan, TSAN_ENV, dict(sanitize="thread", plant=PLANT), ["windowed"]),
+    }
+
+    def one(name):
+        runtime, env, build_kw, cases = plan[name]
+        if runtime is None:
+            return "no such sanitizer runtime in this toolchain"
+        if not _preload_works(runtime, env):
+            return "a Python child does not start with this sanitizer runtime preloaded here"
+        so = build_emu.build(os.path.join(root, name), **build_kw)
+        return _run(so, runtime, env, cases)
+    with ThreadPoolExecutor(max_workers=3) as ex:
+        futs = {k: ex.submit(one, k) for k in plan}
+        return {k: f.result() for k, f in futs.items()}
 
 
-def test_kernels_under_address_and_ub_sanitizers(build_dir):
-    asan = _runtime("libasan.so")
-    if asan is None:
-        pytest.skip("no AddressSanitizer runtime in this toolchain")
-    if not _preload_works(asan, ASAN_ENV):
-        pytest.skip("a Python child does not start with the AddressSanitizer runtime preloaded here")
-    so = build_emu.build(os.path.join(build_dir, "asan"), sanitize=True)
-    r = _run(so, asan, ASAN_ENV,
-             ["windowed", "batch_window", "all_candidates", "all_candidates_few_ids", "logits_odd_vocab"])
-    out = r.stdout + r.stderr
+def _result(runs, name):
+    r = runs[name]
+    if isinstance(r, str):
+        pytest.skip(r)
+    return r, r.stdout + r.stderr
+
+
+def test_kernels_under_address_and_ub_sanitizers(runs):
+    r, out = _result(runs, "asan")
     assert r.returncode == 0, out[-4000:]
     assert "ERROR: AddressSanitizer" not in out and "runtime error:" not in out, out[-4000:]
     assert out.count("emu ok") == 5, out[-2000:]
 
 
-def test_kernels_under_thread_sanitizer(build_dir):
-    tsan = _runtime("libtsan.so")
-    if tsan is None:
-        pytest.skip("no ThreadSanitizer runtime in this toolchain")
-    if not _preload_works(tsan, TSAN_ENV):
-        pytest.skip("a Python child does not start with the ThreadSanitizer runtime preloaded here")
-    so = build_emu.build(os.path.join(build_dir, "tsan"), sanitize="thread")
-    r = _run(so, tsan, TSAN_ENV, ["windowed", "batch_window", "executor"])   # executor: two host threads, two handles
-    out = r.stdout + r.stderr
+def test_kernels_under_thread_sanitizer(runs):
+    r, out = _result(runs, "tsan")
     assert r.returncode == 0, out[-4000:]
     assert "WARNING: ThreadSanitizer" not in out, out[-6000:]
     assert out.count("emu ok") == 3, out[-2000:]
 
 
-def test_thread_sanitizer_run_notices_a_missing_barrier(build_dir):
+def test_thread_sanitizer_run_notices_a_missing_barrier(runs):
     """Self-test of the method: with the barrier between building the list keys and ranking them
     taken out of the (copied) split select kernel, the same run reports data races."""
-    tsan = _runtime("libtsan.so")
-    if tsan is None:
-        pytest.skip("no ThreadSanitizer runtime in this toolchain")
-    plant = ("k_select.h",
-             "  if (fs != 0 && fs < l) return;           // outputs of a finished utterance were settled when it finished\n"
-             "  lds_barrier();",
-             "  if (fs != 0 && fs < l) return;\n  /* planted mistake: no barrier here */")
-    if not _preload_works(tsan, TSAN_ENV):
-        pytest.skip("a Python child does not start with the ThreadSanitizer runtime preloaded here")
-    so = build_emu.build(os.path.join(build_dir, "tsan_planted"), sanitize="thread", plant=plant)
-    r = _run(so, tsan, TSAN_ENV, ["windowed"], timeout=600)
-    out = r.stdout + r.stderr
+    r, out = _result(runs, "tsan_planted")
     assert "WARNING: ThreadSanitizer: data race" in out and "k_select_split" in out, out[-3000:]
