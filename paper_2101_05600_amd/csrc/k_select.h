@@ -170,12 +170,14 @@ __device__ __forceinline__ void wave_survivor_fpl(const Params& p, int u, int n,
   }
 }
 
-// windows of up to 128 frames: two frames per lane, one pass; longer ones: four per lane (a pass
-// costs about 1.4 times as much and covers twice as many frames)
+// windows of up to 128 frames: two frames per lane, one pass; up to 256: four per lane (a pass costs
+// about 1.4 times as much and covers twice as many frames); longer ones: eight per lane
 __device__ __forceinline__ void wave_survivor(const Params& p, int u, int n, int cur, const SurvivorIn& in,
                                               int& arg_n, int& arg_b, float& delta_out) {
-  if (in.en - in.s + 1 <= 128) wave_survivor_fpl<2>(p, u, n, cur, in, arg_n, arg_b, delta_out);
-  else wave_survivor_fpl<4>(p, u, n, cur, in, arg_n, arg_b, delta_out);
+  const int W = in.en - in.s + 1;
+  if (W <= 128) wave_survivor_fpl<2>(p, u, n, cur, in, arg_n, arg_b, delta_out);
+  else if (W <= 256) wave_survivor_fpl<4>(p, u, n, cur, in, arg_n, arg_b, delta_out);
+  else wave_survivor_fpl<8>(p, u, n, cur, in, arg_n, arg_b, delta_out);
 }
 
 // How many of the keys s_k2[0 .. 2 * quads) (four per quad, zero padding at the end) exceed `me`,
