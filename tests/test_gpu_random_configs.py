@@ -16,7 +16,7 @@ from test_gpu_parity import small
 
 pytestmark = pytest.mark.gpu
 
-RUNS = [(1, 60), (2, 40)]          # (seed of the list, cases): every case ran on the CPU build first
+RUNS = [(1, 60), (2, 40), (3, 30)]          # (seed of the list, cases): every case ran on the CPU build first
 
 
 def case_params(case, seed0=1):
