@@ -54,6 +54,13 @@ def parse():
                          "recordings (cfg3: 32 synthetic long recordings cut into segments, sorted by length, "
                          "batches of the workload's size, --inflight batches in flight on --threads host threads) "
                          "and print one JSON line for the job")
+    ap.add_argument("--floor", action="store_true",
+                    help="instead of the benchmark line: time the measurement kernels of csrc/probe.hip -- launches "
+                         "with the score kernel's shape that perform its chain of dependent loads (record, "
+                         "attention row, candidate columns) and next to no arithmetic -- and a sweep of empty launches")
+    ap.add_argument("--floor-live", type=float, default=0.475,
+                    help="--floor: fraction of the (utterance, beam) slots that hold a hypothesis (0.475 is the "
+                         "average over a cfg2 decode, 0.86 its value at step 60)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (known traffic, for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -80,9 +87,13 @@ class Batch:
                                    self.d_ctc.data_ptr(), self.stream)
         assert rc == 0, f"gen_dev_ctc: hip error {rc}"
         torch.cuda.synchronize()
+        # timed decodes keep the per-candidate arrays on chip; the recording decode leaves them in
+        # device memory for an observer (the full-size parity tests read them with ctcbs_peek)
+        kw = {k: v for k, v in w.items() if k not in ("n_utt", "stream", "keep_candidates")}
         self.cfg = m.make_config(n_utt=self.U, t_max=self.t_max, poll_every=poll_every,
-                                 stream=self.stream,
-                                 **{k: v for k, v in w.items() if k not in ("n_utt", "stream")})
+                                 stream=self.stream, keep_candidates=0, **kw)
+        self.cfg_rec = m.make_config(n_utt=self.U, t_max=self.t_max, poll_every=poll_every,
+                                     stream=self.stream, keep_candidates=1, **kw)
         self.l_cap = int(max(self._cap(int(t)) for t in self.lens))
         self.att = None
         self.n_steps = 0
@@ -104,7 +115,7 @@ class Batch:
         U, Wb, V = self.U, self.Wb, self.V
         self.att = torch.empty((self.l_cap, U, Wb, V), dtype=torch.float32, device="cuda")
         hashes = [torch.zeros((U, Wb), dtype=torch.int64, device="cuda") for _ in range(2)]
-        h = m.ctcbs_create(self.cfg, self.d_ctc, self.lens)
+        h = m.ctcbs_create(self.cfg_rec if observer is not None else self.cfg, self.d_ctc, self.lens)
         out = m.StepOut()
         G = gen.dev()
         step = 0
@@ -186,7 +197,7 @@ class Batch:
             self.hs = []
             for st in self.streams:
                 cfg = m.make_config(n_utt=self.U, t_max=self.t_max, poll_every=self.poll_every,
-                                    stream=st.cuda_stream,
+                                    stream=st.cuda_stream, keep_candidates=0,
                                     **{k: v for k, v in self.w.items() if k not in ("n_utt", "stream")})
                 self.hs.append(m.ctcbs_create(cfg, self.d_ctc, self.lens))
         results = [None] * n_jobs
@@ -325,7 +336,7 @@ def run_job(a):
     streams = [torch.cuda.Stream() for _ in range(n_slots)]
     hs = []
     for st in streams:
-        cfg = m.make_config(n_utt=U, t_max=t_max, poll_every=a.poll_every, stream=st.cuda_stream,
+        cfg = m.make_config(n_utt=U, t_max=t_max, poll_every=a.poll_every, stream=st.cuda_stream, keep_candidates=0,
                             **{k: v for k, v in w.items() if k not in ("n_utt", "stream")})
         hs.append(m.ctcbs_create(cfg, batches[0].d_ctc, batches[0].lens))
     results = [None] * len(batches)
@@ -374,6 +385,81 @@ def run_job(a):
                    "decode_steps_total": sum(b.n_steps for b in batches), "cells_per_job": cells}}))
 
 
+def floor(a):
+    """Latency floor of one score launch at the headline shape (U=64, beam 10, V=5000, top-40, window
+    50/50): the chain of dependent loads alone.  Synthetic buffers of the real sizes; every repetition
+    reads attention rows and candidate columns it has not touched before, and the records are rewritten by
+    a small kernel between launches (as the select kernel does in a decode).  Prints a table: average
+    launch-to-launch period of back-to-back dependent launches on one stream (HIP events around the
+    whole series), which is what a decode pays per launch.  Per-kernel durations come from running this
+    under rocprofv3 --kernel-trace (the kernels of each level have their own names)."""
+    import torch
+    import paper_2101_05600_amd as m
+    P = m.probe_lib()
+    w = __import__("gen").workload(a.workload)
+    U, Wb, V, K = (a.utts or w["n_utt"]), w["beam"], w["vocab"], w["cand_k"]
+    T = 875
+    Tp = ((T + 5 + 31) // 32) * 32
+    G = U * Wb
+    reps = 24
+    st = torch.cuda.current_stream().cuda_stream
+    gcpu = torch.Generator().manual_seed(1234)
+    att = torch.randn((8, G, V), device="cuda")
+    xT = torch.empty((U, V, Tp), device="cuda").normal_()
+    cand = torch.randint(1, V - 1, (reps, G, K), generator=gcpu, dtype=torch.int32).cuda()
+    sink = torch.zeros(G * 4, device="cuda")
+    out = []
+    for live_frac in (a.floor_live,):
+        rec = np.zeros((G, 16), np.int32)                # 64-byte records: live, last, rs, re, tau, tau_end, ref, pad, 4 doubles
+        rng = np.random.default_rng(7)
+        rec[:, 0] = rng.random(G) < live_frac
+        tau = rng.integers(60, T - 60, G)
+        rec[:, 2] = 0; rec[:, 3] = T; rec[:, 4] = tau; rec[:, 5] = tau + 2; rec[:, 6] = tau
+        rec_src = torch.from_numpy(rec).cuda()
+        rec_dst = torch.empty_like(rec_src)
+        for level in range(4):
+            def series(n):
+                for r in range(n):
+                    P.probe_touch(rec_src.data_ptr(), rec_dst.data_ptr(), G, st)
+                    rc = P.probe_chain(level, rec_dst.data_ptr(), att[r % 8].data_ptr(), xT.data_ptr(),
+                                       cand[r % reps].data_ptr(), sink.data_ptr(), U, Wb, V, Tp, K,
+                                       w["win_m1"], w["win_m2"], 15 * 1024, st)
+                    assert rc == 0, rc
+            series(4)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(); series(reps); e1.record()
+            torch.cuda.synchronize()
+            pair_us = e0.elapsed_time(e1) * 1e3 / reps
+            e0.record()
+            for r in range(reps):
+                P.probe_touch(rec_src.data_ptr(), rec_dst.data_ptr(), G, st)
+            e1.record()
+            torch.cuda.synchronize()
+            touch_us = e0.elapsed_time(e1) * 1e3 / reps
+            out.append((live_frac, level, pair_us - touch_us))
+    print("| live groups | level | launch-to-launch period, us (touch kernel's own period taken out) |")
+    print("|---|---|---|")
+    names = ["0 nothing", "1 + record", "2 + attention row", "3 + candidate columns"]
+    for lf, lv, us in out:
+        print(f"| {int(round(lf * G))} of {G} | {names[lv]} | {us:.2f} |")
+    print()
+    print("| empty launch: work-groups x threads, LDS bytes, argument bytes | period, us |")
+    print("|---|---|")
+    for groups, threads, lds, big in ((G, 256, 15 * 1024, 1), (G, 256, 0, 1), (G, 256, 0, 0), (G, 64, 0, 0),
+                                      (U, 256, 0, 0), (U, 1024, 0, 0), (8 * G, 256, 15 * 1024, 1), (1, 64, 0, 0)):
+        for _ in range(4):
+            P.probe_empty(groups, threads, lds, big, st)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(200):
+            P.probe_empty(groups, threads, lds, big, st)
+        e1.record()
+        torch.cuda.synchronize()
+        print(f"| {groups} x {threads}, {lds}, {704 if big else 12} | {e0.elapsed_time(e1) * 1e3 / 200:.2f} |")
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -387,6 +473,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     m.lib()
+    if a.floor:
+        floor(a)
+        return
     if a.sweep:
         sweep(a)
         return

@@ -94,6 +94,11 @@ typedef struct {
   int32_t att_is_logits; /* 0: ctcbs_step takes log-probabilities p^a; 1: it takes the decoder's
                            unnormalised output scores and applies log_softmax over the V ids of
                            each row itself (folded into the candidate pass; Eq. (2)'s p^a)  */
+  int32_t keep_candidates; /* 1: every step also leaves each hypothesis's candidate ids and their
+                           prefix / joint scores in device memory for ctcbs_peek (checking and
+                           inspection; costs a few per cent of the step's memory traffic);
+                           0: they stay on chip and ctcbs_peek of them returns CTCBS_ESTATE.
+                           Step outputs and results are the same either way.               */
   void* stream;         /* hipStream_t; NULL = the null stream                             */
 } ctcbs_config_t;
 
@@ -142,9 +147,12 @@ int ctcbs_reset(ctcbs_t* h, const float* d_ctc_logp, const int32_t* h_lens);
  * One iteration of Algorithm 2's loop (Score_Fn with Eq. (1)-(3)/(5), eos split-off, TopB,
  * GatherB, the "p > best_score" test, ENDDETECT) for all utterances.
  * d_att_logp[u][j][k] = log p^a(y^l = k | hypothesis in beam slot j of utterance u) (device,
- * fp32, [U][Wb][V]); rows of dead slots and finished utterances are not read.  At the first
- * step only slot 0 of each utterance is live.  The buffer must stay valid until the step's
- * work has run on the stream.  `out` may be NULL.
+ * fp32, [U][Wb][V], the whole buffer valid device memory); rows of dead slots and finished
+ * utterances may be fetched but their contents are never looked at (garbage and NaN are fine).
+ * At the first step only slot 0 of each utterance is live.  The buffer must stay valid until
+ * the step's work has run on the stream.  Rows that start on 16-byte boundaries (d_att_logp
+ * 16-byte aligned and V a multiple of 4) take the fast candidate selection; any other
+ * alignment is accepted and takes a slower, equivalent path.  `out` may be NULL.
  * Returns CTCBS_DONE (and enqueues nothing) once the handle knows that all utterances are
  * finished: after a look or ctcbs_poll saw it, or when the step index passes every
  * utterance's cap.  Steps enqueued after the last utterance finished do nothing.

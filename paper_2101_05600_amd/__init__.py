@@ -30,10 +30,34 @@ EXPORTS = ["ctcbs_create", "ctcbs_step", "ctcbs_poll", "ctcbs_finalize", "ctcbs_
            "ctcbs_plan_batches", "ctcbs_run_many", "ctcbs_att_replay", "ctcbs_run_queue"]
 
 
+_PROBE_SO = os.path.join(_HERE, "libctcbs_probe.so")
+_probe = None
+
+
 def build():
-    """Compile the HIP library for gfx950 (cross-compiles without a GPU)."""
+    """Compile the HIP library for gfx950 (cross-compiles without a GPU), and the measurement
+    kernels of the latency floor (their own small library: not part of the decoding path)."""
     src = os.path.join(_HERE, "csrc", "ctcbs.hip")
     subprocess.check_call(["hipcc", *HIP_FLAGS, "-o", _SO, src])
+    subprocess.check_call(["hipcc", *HIP_FLAGS, "-o", _PROBE_SO, os.path.join(_HERE, "csrc", "probe.hip")])
+
+
+def probe_lib():
+    """The measurement kernels of csrc/probe.hip (bench.py --floor)."""
+    global _probe
+    if _probe is None:
+        if not os.path.exists(_PROBE_SO):
+            raise RuntimeError(f"{_PROBE_SO} is missing: run __graft_entry__.build() first")
+        L = ctypes.CDLL(_PROBE_SO)
+        vp, i32 = ctypes.c_void_p, ctypes.c_int32
+        L.probe_chain.restype = i32
+        L.probe_chain.argtypes = [i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp]
+        L.probe_empty.restype = i32
+        L.probe_empty.argtypes = [i32, i32, i32, i32, vp]
+        L.probe_touch.restype = i32
+        L.probe_touch.argtypes = [vp, vp, i32, vp]
+        _probe = L
+    return _probe
 
 
 class Config(ctypes.Structure):
@@ -45,7 +69,7 @@ class Config(ctypes.Structure):
                 ("end_flags", ctypes.c_int32), ("end_m", ctypes.c_int32), ("end_d", ctypes.c_float),
                 ("end_c", ctypes.c_int32), ("eos_run", ctypes.c_int32), ("poll_every", ctypes.c_int32),
                 ("win_union", ctypes.c_int32), ("att_is_logits", ctypes.c_int32),
-                ("stream", ctypes.c_void_p)]
+                ("keep_candidates", ctypes.c_int32), ("stream", ctypes.c_void_p)]
 
 
 class StepOut(ctypes.Structure):
@@ -128,7 +152,7 @@ def _ptr(t):
 def make_config(n_utt, t_max, vocab, beam, blank_id=0, eos_id=None, cand_k=0, win_m1=-1, win_m2=-1,
                 ctc_weight=0.3, length_bonus=0.0, max_len_ratio=0.0, max_len_abs=0, end_flags=3,
                 end_m=3, end_d=-10.0, end_c=2, eos_run=10, poll_every=0, stream=None, att_is_logits=0,
-                win_union=0, **_ignored):
+                win_union=0, keep_candidates=1, **_ignored):
     c = Config()
     c.n_utt, c.t_max, c.vocab, c.beam, c.blank_id = n_utt, t_max, vocab, beam, blank_id
     c.eos_id = vocab - 1 if eos_id is None else eos_id
@@ -139,6 +163,7 @@ def make_config(n_utt, t_max, vocab, beam, blank_id=0, eos_id=None, cand_k=0, wi
     c.poll_every = poll_every
     c.att_is_logits = att_is_logits
     c.win_union = win_union
+    c.keep_candidates = keep_candidates
     c.stream = stream
     return c
 

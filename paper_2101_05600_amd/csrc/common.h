@@ -2,10 +2,12 @@
 //
 // Numeric form.  Every hypothesis g keeps its two CTC forward variables (paths ending in
 // its last label / ending in blank; their log-sum is the paper's phi_t(g) of Eq. (3)) as
-// fp32 values RELATIVE to an fp64 offset off(g) = log psi(g), the hypothesis's own prefix
-// score.  Near the frames that matter the relative values are O(1), so fp32 keeps ~1e-6
-// absolute accuracy no matter how negative the cumulative score has become; cumulative
-// CTC, attention and joint scores are accumulated in fp64, one add per hypothesis and step.
+// fp32 values in a STORED form: gamma_t(g) = stored_t + B_t + off'(g), with B_t the
+// utterance's cumulative blank log-posterior (fp64, Params::Bcum) and off'(g) an fp64 offset
+// per hypothesis (HypRec::off).  Staying in blank leaves the stored value unchanged, so stored
+// values are O(1) near the frames that matter however long the utterance is and however
+// negative the cumulative score has become; the parts that grow (B_t, off') and the cumulative
+// CTC, attention and joint scores are fp64, one add per hypothesis and step.
 // log0 is the finite sentinel -1e30 (anything below -1e29 is treated as log0).
 #pragma once
 #include <hip/hip_runtime.h>
@@ -52,6 +54,26 @@ struct UttState {            // per utterance, touched by one thread of the sele
   int32_t pad;
 };
 
+// One hypothesis of the current beam: a 64-byte line, so that a work-group fetches the whole
+// record of its hypothesis with one uniform (scalar-path) load.
+struct __align__(64) HypRec {
+  int32_t live;              // slot holds a hypothesis
+  int32_t last;              // its last label (-1: the empty hypothesis)
+  int32_t rs, re;            // stored range of its forward variables (log0 outside)
+  int32_t tau, tau_end;      // first argmax of the label / blank variable (the two argmax equations of Sec. 3.2.2)
+  int32_t ref;               // reference frame r: prefix-score increments are relative to off' + B_r
+  int32_t pad;
+  double off;                // off'(g): log psi(g) = off'(g) + B_r(g) up to the rounding of the re-basing
+  double att;                // cumulative attention log-prob, Eq. (2)
+  double joint;              // joint score of the hypothesis, Eq. (1)
+  double bref;               // B_r (copied from Bcum so that no load depends on `ref`)
+};
+
+struct UttInfo {             // per utterance, constant over a decode
+  int32_t T, lmax;           // frames, step cap
+  double BT;                 // B_T
+};
+
 struct Params {
   // sizes and configuration
   int32_t U, V, Wb, K, Tp, t_max, blank_id, eos_id;
@@ -71,20 +93,13 @@ struct Params {
   // stored value does not change from frame to frame, so stored values stay within tens of nats of
   // zero however long the utterance is, and the large part (B_t) is carried in fp64.
   double* Bcum;
+  UttInfo* uinfo;            // [U]
   // hypothesis state, two buffers (index b): forward variables [b][U][Wb][Tp] (stored form) and
   // per-hypothesis records [b][U][Wb]
   float* gn[2];
   float* gb[2];
-  int32_t* h_live[2];
-  int32_t* h_last[2];
-  int32_t* h_rs[2];
-  int32_t* h_re[2];
-  int32_t* h_tau[2];
-  int32_t* h_tau_end[2];
-  int32_t* h_ref[2];         // reference frame r: prefix-score increments are relative to off' + B_r
-  double* h_off[2];          // off'(g): log psi(g) = off'(g) + B_r(g) up to the rounding of the re-basing
-  double* h_att[2];          // cumulative attention log-prob, Eq. (2)
-  double* h_joint[2];        // joint score of the hypothesis
+  HypRec* rec[2];
+  int32_t keep_cand;         // 1: the per-candidate arrays below are filled every step (ctcbs_peek; large K needs them)
   // per-step scratch between the score and the select kernel
   int32_t* win_s;            // [U][Wb]
   int32_t* win_e;

@@ -125,6 +125,7 @@ static int validate(const ctcbs_config_t* c) {
   if (c->poll_every < 0) return CTCBS_EINVAL;
   if (c->att_is_logits != 0 && c->att_is_logits != 1) return CTCBS_EINVAL;
   if (c->win_union != 0 && c->win_union != 1) return CTCBS_EINVAL;
+  if (c->keep_candidates != 0 && c->keep_candidates != 1) return CTCBS_EINVAL;
   if ((long long)c->n_utt * c->beam > (1ll << 24)) return CTCBS_EINVAL;
   return CTCBS_OK;
 }
@@ -194,6 +195,8 @@ static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens)
   p.lambda = (double)c.ctc_weight; p.beta = (double)c.length_bonus;
   p.att_logits = c.att_is_logits ? 1 : 0;
   p.win_union = c.win_union ? 1 : 0;
+  // large candidate sets go through the per-candidate arrays in global memory whatever the caller asked for
+  p.keep_cand = (c.keep_candidates || K > 256 || !restricted) ? 1 : 0;
 
   // capacity for any batch of lengths <= t_max (the step cap grows with the length)
   h->l_cap_alloc = step_cap(&c, c.t_max);
@@ -210,13 +213,15 @@ static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens)
   p.lens = d_lens; p.lmax = d_lmax;
   for (int b = 0; b < 2; ++b) {
     A(p.gn[b], UW * p.Tp); A(p.gb[b], UW * p.Tp);
-    A(p.h_live[b], UW); A(p.h_last[b], UW); A(p.h_rs[b], UW); A(p.h_re[b], UW);
-    A(p.h_tau[b], UW); A(p.h_tau_end[b], UW); A(p.h_ref[b], UW);
-    A(p.h_off[b], UW); A(p.h_att[b], UW); A(p.h_joint[b], UW);
+    A(p.rec[b], UW);
   }
+  A(p.uinfo, (size_t)U);
   A(p.win_s, UW); A(p.win_e, UW);
-  A(p.cand_id, UW * K); A(p.cand_inc, UW * K); A(p.cand_att, UW * K); A(p.cand_pre, UW * K);
-  A(p.cand_ctc, UW * K); A(p.cand_joint, UW * K);
+  {
+    const size_t nc = p.keep_cand ? UW * K : 1;            // (not kept: never touched)
+    A(p.cand_id, nc); A(p.cand_inc, nc); A(p.cand_att, nc); A(p.cand_pre, nc);
+    A(p.cand_ctc, nc); A(p.cand_joint, nc);
+  }
   A(p.grp_n, UW); A(p.grp_J, UW * Wb); A(p.grp_ci, UW * Wb); A(p.grp_tok, UW * Wb);
   A(p.grp_inc, UW * Wb); A(p.grp_att, UW * Wb);
   A(p.ctc_eos, UW); A(p.joint_eos, UW); A(p.stopped, UW); A(p.grp_cells, UW);
@@ -325,8 +330,11 @@ template <int BLOCK, int LPC, int CB, int IT>
 static hipError_t launch_score(ctcbs* h, const float* att, int l) {
   hipError_t ea = allow_lds((const void*)k_score<BLOCK, LPC, CB, IT>, h->score_smem_bytes);
   if (ea != hipSuccess) return ea;
-  hipLaunchKernelGGL((k_score<BLOCK, LPC, CB, IT>), dim3(h->p.U * h->p.Wb), dim3(BLOCK), h->score_smem_bytes,
-                     h->stream, h->p, h->sm, att, l, h->cur);
+  // attention rows that do not start on 16-byte boundaries cannot be loaded as float4: the candidate
+  // selection then reads them element by element (slower, equivalent)
+  const int flags = (((uintptr_t)att & 15) == 0 && h->p.V % 4 == 0) ? 1 : 0;
+  hipLaunchKernelGGL((k_score<BLOCK, LPC, CB, IT>), dim3(h->p.Wb, h->p.U), dim3(BLOCK), h->score_smem_bytes,
+                     h->stream, h->p, h->sm, att, l, h->cur, flags);
   return hipGetLastError();
 }
 
@@ -512,6 +520,8 @@ extern "C" int ctcbs_peek(ctcbs_t* h, int32_t what, void* h_dst, size_t bytes, s
   const size_t UW = (size_t)p.U * p.Wb;
   const void* src = nullptr; size_t sz = 0;
   int32_t k = p.K;
+  if (!p.keep_cand && (what == CTCBS_PEEK_CAND_ID || what == CTCBS_PEEK_CAND_CTC || what == CTCBS_PEEK_CAND_JOINT))
+    return CTCBS_ESTATE;                                   // created without keep_candidates
   switch (what) {
     case CTCBS_PEEK_CAND_ID: src = p.cand_id; sz = UW * p.K * 4; break;
     case CTCBS_PEEK_CAND_CTC: src = p.cand_ctc; sz = UW * p.K * 8; break;

@@ -23,7 +23,7 @@ __global__ __launch_bounds__(BLOCK) void k_finalize(Params p, int cur, int steps
       flag = 1;
       // beam of the last step this utterance took part in; slot 0 is its best hypothesis
       const size_t h = (size_t)u * Wb;
-      if (!st.finished_step && p.h_live[cur][h]) { level = steps_done; slot = 0; sc = p.h_joint[cur][h]; }
+      if (!st.finished_step && p.rec[cur][h].live) { level = steps_done; slot = 0; sc = p.rec[cur][h].joint; }
       else { level = 0; slot = 0; sc = LOG0D; }
     }
     flags[u] = flag;

@@ -113,19 +113,22 @@ __global__ __launch_bounds__(64) void k_init_state(Params p, int n_empty) {
   for (int t = T + 1 + lane; t < p.Tp; t += 64) Bu[t] = carry;   // (never weighted: keeps reads defined)
   for (int j = lane; j < p.Wb; j += 64) {
     size_t h = hyp0 + j;
-    p.h_live[0][h] = (j == 0 && T > 0); p.h_last[0][h] = -1;
-    p.h_rs[0][h] = 0; p.h_re[0][h] = T; p.h_tau[0][h] = 0; p.h_tau_end[0][h] = 0; p.h_ref[0][h] = 0;
-    p.h_off[0][h] = 0.0; p.h_att[0][h] = 0.0; p.h_joint[0][h] = 0.0;
+    HypRec r;
+    r.live = (j == 0 && T > 0); r.last = -1; r.rs = 0; r.re = T; r.tau = 0; r.tau_end = 0; r.ref = 0; r.pad = 0;
+    r.off = 0.0; r.att = 0.0; r.joint = 0.0; r.bref = 0.0;
+    p.rec[0][h] = r;
     // the other buffer: dead until the first selection fills it, but never left holding what the
     // allocation happened to contain (a kernel may load a dead slot's record before it looks at its flag)
-    p.h_live[1][h] = 0; p.h_last[1][h] = -1;
-    p.h_rs[1][h] = 0; p.h_re[1][h] = T; p.h_tau[1][h] = 0; p.h_tau_end[1][h] = 0; p.h_ref[1][h] = 0;
-    p.h_off[1][h] = 0.0; p.h_att[1][h] = 0.0; p.h_joint[1][h] = 0.0;
+    r.live = 0;
+    p.rec[1][h] = r;
     p.out_live[h] = (j == 0 && T > 0); p.out_parent[h] = 0; p.out_token[h] = -1; p.out_score[h] = 0.0f;
     p.out_tau[h] = 0; p.out_tau_end[h] = 0; p.out_eos_added[h] = 0; p.out_stopped[h] = 0;
     p.trie_parent[h] = 0; p.trie_token[h] = -1; p.trie_tau[h] = 0;   // level 0: the empty hypothesis
   }
   if (lane == 0) {
+    UttInfo ui;
+    ui.T = T; ui.lmax = p.lmax[u]; ui.BT = carry;          // (B_T: the running sum after the last frame; 0 for T = 0)
+    p.uinfo[u] = ui;
     UttState s;
     s.best_score = LOG0D; s.fb_score = LOG0D;
     for (int i = 0; i < MAX_END_M; ++i) { s.ring_score[i] = LOG0D; s.ring_tag[i] = -1; }

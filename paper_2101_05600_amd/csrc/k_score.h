@@ -1,7 +1,8 @@
 // Score kernel: one work-group per (utterance, beam slot) hypothesis g.
 //   1. candidate pre-selection: the K ids with the largest attention log-prob, ties to the
 //      smaller id.  The row never goes through LDS: every lane keeps its float4 loads in
-//      registers.  Fast path: a pivot L that is provably not above
+//      registers.  Fast path: a
+//      pivot L that is provably not above
 //      the K-th largest value (every wave contributes the ceil(K/#waves)-th largest of its
 //      lanes' maxima, found by bisection on the upper key bits), then an exact ranking of the
 //      few values >= L.  Rows that do not fit the registers, or with so many values >= L that
@@ -19,15 +20,15 @@
 #pragma once
 #include "common.h"
 
-#define PIVOT_CAP 512     // entries of the short list
+#define PIVOT_CAP 512     // entries of the short list (all waves together)
 #define PIVOT_NV4 6       // float4 loads per lane held in registers (rows of up to 6144 ids)
 #define RADIX_BITS 10
 
 struct ScoreSmem {
   // byte offsets into dynamic LDS, computed on the host
-  int32_t off_work;   // union: uint32 hist[1 << RADIX_BITS] | { uint32 key[CAP + 4]; int32 idx[CAP + 4] }
+  int32_t off_work;   // union: uint32 hist[1 << RADIX_BITS] | short list of the pivot selection
   int32_t off_f;      // float F[wp_max], Fb[wp_max]
-  int32_t off_small;  // double J[Ks]; int32 cand_id[Ks]; float inc[Ks], att[Ks], pre[Ks]; double Jraw[Ks]  (Ks = K if K <= BLOCK else 0)
+  int32_t off_small;  // per-candidate arrays of the group (K <= block size), see k_score
   int32_t wp_max;     // floats available per F array
 };
 
@@ -183,7 +184,8 @@ __device__ __noinline__ void select_radix(const float* __restrict__ arow, int V,
     krem = s_sel[1];
   }
   // prefix = key of the K-th best; krem = how many of the keys equal to it are taken
-  // (those with the smallest ids).  Ordered compaction, contiguous id chunk per thread.
+  // (those with the smallest ids).  Ordered compaction, contiguous id chunk per thread; the
+  // two counts are scanned separately (either can be as large as the row).
   const int chunk = (V + BLOCK - 1) / BLOCK;
   const int i0 = min(V, tid * chunk), i1 = min(V, i0 + chunk);
   uint32_t gt = 0, eq = 0;
@@ -192,8 +194,8 @@ __device__ __noinline__ void select_radix(const float* __restrict__ arow, int V,
     gt += (k > prefix); eq += (k == prefix);
   }
   uint32_t total;
-  uint32_t ex = block_excl_scan_u32<BLOCK>((gt << 16) | eq, s_scan, &total);
-  uint32_t gt_before = ex >> 16, eq_before = ex & 0xffffu;
+  const uint32_t gt_before = block_excl_scan_u32<BLOCK>(gt, s_scan, &total);
+  uint32_t eq_before = block_excl_scan_u32<BLOCK>(eq, s_scan, &total);
   uint32_t pos = gt_before + min(eq_before, krem);
   for (int i = i0; i < i1; ++i) {
     const float a = arow[i];
@@ -213,15 +215,6 @@ struct Lse { float m, s; };
 
 __device__ __forceinline__ void lse_add4(Lse& a, const float4 x, const float4 f) {
   const float v0 = f.x + x.x, v1 = f.y + x.y, v2 = f.z + x.z, v3 = f.w + x.w;
-  const float mn = fmaxf(a.m, fmaxf(fmaxf(v0, v1), fmaxf(v2, v3)));
-  a.s = a.s * __expf(a.m - mn) + (__expf(v0 - mn) + __expf(v1 - mn)) + (__expf(v2 - mn) + __expf(v3 - mn));
-  a.m = mn;
-}
-
-// the same, counting only frames <= t_cut (tb = frame of x.x)
-__device__ __forceinline__ void lse_add4_upto(Lse& a, const float4 x, const float4 f, int tb, int t_cut) {
-  const float v0 = tb <= t_cut ? f.x + x.x : LOG0F, v1 = tb + 1 <= t_cut ? f.y + x.y : LOG0F;
-  const float v2 = tb + 2 <= t_cut ? f.z + x.z : LOG0F, v3 = tb + 3 <= t_cut ? f.w + x.w : LOG0F;
   const float mn = fmaxf(a.m, fmaxf(fmaxf(v0, v1), fmaxf(v2, v3)));
   a.s = a.s * __expf(a.m - mn) + (__expf(v0 - mn) + __expf(v1 - mn)) + (__expf(v2 - mn) + __expf(v3 - mn));
   a.m = mn;
@@ -267,9 +260,20 @@ __device__ __forceinline__ double block_sum_d(float sum, double* s_d /*[BLOCK / 
   return tot;
 }
 
+// Order-preserving 64-bit image of a joint score with the token in its 16 lowest mantissa bits:
+// one integer comparison then orders by (score descending, token ascending); scores equal to
+// within 2^-36 relative count as equal.  0 = not a competitor.  Needs token ids below 65536.
+__device__ __forceinline__ unsigned long long joint_key(double J, int tok, bool valid) {
+  if (!valid) return 0ull;
+  const unsigned long long b = (unsigned long long)__double_as_longlong(J);
+  const unsigned long long k = (b >> 63) ? ~b : (b | 0x8000000000000000ull);
+  return (k & ~0xFFFFull) | (unsigned long long)(0xFFFF - tok);
+}
+
+// Grid: (Wb, U).  flags bit 0: the attention rows start on 16-byte boundaries.
 template <int BLOCK, int LPC, int CB, int IT>
 __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p, ScoreSmem sm, const float* __restrict__ att,
-                                                 int l, int cur) {
+                                                 int l, int cur, int flags) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ uint32_t s_scan[BLOCK / 64 + 1];
   __shared__ uint32_t s_w[2 * (BLOCK / 64)];
@@ -277,39 +281,40 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p
   __shared__ float s_e2w[(BLOCK / 64) * MAX_EOS_RUN + 1];
   __shared__ int s_nvalid;
   __shared__ __align__(8) float s_red[4 * (BLOCK / 64)];   // BLOCK/64 floats, then BLOCK/64 doubles
+  __shared__ double s_eos[2];                              // eos scores, computed early, written at the end
 
   const int tid = threadIdx.x;
-  const int grp = blockIdx.x;
+  const int u = blockIdx.y;
+  const int grp = u * p.Wb + blockIdx.x;
   TRACE_DECL;
-  const int u = grp / p.Wb;
   const int K = p.K, V = p.V;
   const bool smallk = (K <= BLOCK);
 
-  // ---------------- first round of loads: g's record, then its attention row ----------------
-  // The record comes through the scalar path (uniform addresses, nothing in this kernel writes
-  // them before): it is back in a fraction of a vector load's latency and is not ordered behind
-  // the row loads issued next.  A dead slot's row is never read: half of the groups of a
-  // typical batch are dead on average (utterances finish at different steps).
+  // ---------------- first round of loads: the attention row and g's record -------------------
+  // The row loads need nothing but the kernel's arguments and go first, all in flight together
+  // (clamped, unconditional: whether the slot holds a hypothesis is only known once its record
+  // is back, and a dead slot's row is valid memory whose values are never looked at).  The
+  // record, one 64-byte line, comes through the scalar path (uniform address, nothing in this
+  // kernel writes it), as do the utterance's constants.
+  const float* arow = att + (size_t)grp * V;
+  const bool in_regs = p.restricted && (V & 3) == 0 && (V >> 2) <= PIVOT_NV4 * BLOCK && (flags & 1);
+  float4 arow_r[PIVOT_NV4];
+  const HypRec rec = p.rec[cur][grp];
+  const UttInfo ui = p.uinfo[u];
   // (the utterance's finished byte is fetched as part of its aligned word: a uniform word load
   // can take the scalar path, a byte load cannot)
   const uint32_t fin_word = ((const uint32_t*)p.finished)[u >> 2];
-  const int dead = (int)((fin_word >> (8 * (u & 3))) & 0xffu) | (p.h_live[cur][grp] == 0);
-  const int T = p.lens[u];
-  const int tau = p.h_tau[cur][grp], tau_end = p.h_tau_end[cur][grp];
-  const int rs = p.h_rs[cur][grp], re = p.h_re[cur][grp], last = p.h_last[cur][grp];
-  const int ref = p.h_ref[cur][grp];
-  const double off = p.h_off[cur][grp], acum = p.h_att[cur][grp];
-  const float* arow = att + (size_t)grp * V;
-  // attention row -> registers (restricted mode, rows that fit): PIVOT_NV4 float4 per lane, all
-  // in flight together (clamped, unconditional for a live slot)
-  const bool in_regs = p.restricted && (V & 3) == 0 && (V >> 2) <= PIVOT_NV4 * BLOCK;
-  float4 arow_r[PIVOT_NV4];
+  const int dead = (int)((fin_word >> (8 * (u & 3))) & 0xffu) | (rec.live == 0);
   if (in_regs && !dead) {
     const float4* a4 = (const float4*)arow;
     const int nv4 = V >> 2;
 #pragma unroll
     for (int k = 0; k < PIVOT_NV4; ++k) arow_r[k] = a4[min(tid + k * BLOCK, nv4 - 1)];
   }
+  const int T = ui.T;
+  const int tau = rec.tau, tau_end = rec.tau_end;
+  const int rs = rec.rs, re = rec.re, last = rec.last;
+  const double off = rec.off, acum = rec.att;
   // publish the count of finished utterances (as of the previous step) where the host can
   // read it without synchronising: one writer, plain store to device-mapped pinned memory
   if (grp == 0 && tid == 0) {
@@ -331,13 +336,15 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p
   uint32_t* s_work = (uint32_t*)(smem + sm.off_work);
   float* s_F = (float*)(smem + sm.off_f);
   float* s_Fb = s_F + sm.wp_max;
+  // per-candidate arrays of the group (K <= BLOCK): sort key and joint score (8 bytes each), then
+  // id, prefix-score increment, attention value, eos-run scratch (4 bytes each)
   const int Ks = smallk ? K : 0;
-  double* s_J = (double*)(smem + sm.off_small);
-  int32_t* s_cid = (int32_t*)(s_J + Ks);                  // only touched when smallk
-  float* s_inc = (float*)(smem + sm.off_small) + 3 * Ks;    // after J (2 words each) and cand_id
+  unsigned long long* s_key = (unsigned long long*)(smem + sm.off_small);
+  double* s_J = (double*)(s_key + Ks);                     // joint score as computed (NaN kept)
+  int32_t* s_cid = (int32_t*)(s_J + Ks);                   // only touched when smallk
+  float* s_inc = (float*)(s_cid + Ks);
   float* s_av = s_inc + Ks;
   float* s_pre = s_av + Ks;                                // eos-run rule: prefix score without the last R frames
-  double* s_Jraw = (double*)(s_pre + Ks);                  // joint score as computed (NaN kept), for the global copy (6 Ks floats in: 8-byte aligned)
   int32_t* g_cid = p.cand_id + (size_t)grp * K;
 
   // logits mode: the row holds unnormalised scores; log_softmax is folded in here (the order of
@@ -387,12 +394,12 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p
   // Stored forward variables have the per-frame reference B_t taken out (see Params::Bcum); all
   // increments of this step are relative to off'(g) + B_r, r = g's reference frame
   const double* Bu = p.Bcum + (size_t)u * p.Tp;
-  const double Bref = Bu[checked(p, ref, 0, T, ERR_TIME_INDEX)];
+  const double Bref = rec.bref;
   const double offr = off + Bref;
+  const double BT = ui.BT - Bref;                          // B_T - B_r
 
-  // eos inputs (thread 0), fetched now so that the epilogue does not wait for them
+  // eos inputs (thread 0), fetched now so that nothing waits for them later
   float eos_n = LOG0F, eos_b = LOG0F, eos_a = 0.0f;
-  const double BT = Bu[T] - Bref;                          // B_T - B_r
   if (tid == 0) {
     if (rs <= T && re >= T) { eos_n = gn[T]; eos_b = gb[T]; }
     eos_a = arow[p.eos_id];               // (logits mode: shifted by the row's log-sum-exp below)
@@ -400,23 +407,35 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p
 
   TRACE_MARK(1);
   // ---------------- stage the f terms of the window in LDS ---------------------------------
-  for (int i = tid; i < Wp; i += BLOCK) {
-    const int t = t0 + i;
-    float f = LOG0F, fb = LOG0F;
+  // gamma_{t-1}(g) - off' - B_r = stored_{t-1} + (B_{t-1} - B_r); far from r the second part is
+  // large and coarse in fp32, and the term is then negligible by that same factor
+  auto f_terms = [&](int t, float& f, float& fb) {
+    f = LOG0F; fb = LOG0F;
     if (t >= s && t <= e) {
       const int pr = t - 1;
       if (pr >= rs && pr <= re) {
-        // gamma_{t-1}(g) - off' - B_r = stored_{t-1} + (B_{t-1} - B_r); far from r the second part is
-        // large and coarse in fp32, and the term is then negligible by that same factor
         const float bt = (float)(Bu[pr] - Bref);
         const float n = gn[pr]; fb = gb[pr]; f = canon0(lae(n, fb) + bt); fb = canon0(fb + bt);
       }
     }
+  };
+  for (int i = tid; i < Wp; i += BLOCK) {
+    float f, fb;
+    f_terms(t0 + i, f, fb);
     s_F[i] = f; s_Fb[i] = fb;
   }
   const int R = p.eos_run;
   const bool e2 = (p.end_flags & 4) && R > 0 && T >= R && W > 0 && e == T && re == T &&
                   max(s, rs) <= T - R + 1;
+  const double lam = p.lambda, jbase = (1.0 - lam) * acum + p.beta * (double)l;
+  if (tid == 0) {
+    // eos: phi_T(g) = off' + B_T + stored
+    const float ce = (rs <= T && re >= T) ? canon0(lae(eos_n, eos_b)) : LOG0F;
+    const bool v = ce > LOG0_CLASS;
+    const double ctc = v ? offr + BT + (double)ce : LOG0D;
+    s_eos[0] = ctc;
+    s_eos[1] = v ? lam * ctc + (1.0 - lam) * (double)(eos_a - row_lse) + jbase : LOG0D;
+  }
   TRACE_MARK(2);
 
   // ---------------- 1. candidates -----------------------------------------------------------
@@ -459,7 +478,7 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p
   constexpr int NSG = BLOCK / LPC;
   const int sg = tid / LPC, q = tid % LPC;
   const float* xu = p.xT + (size_t)u * V * p.Tp;
-  const double lam = p.lambda, jbase = (1.0 - lam) * acum + p.beta * (double)l;
+  const bool wave_rank = smallk && K <= 64 && V <= 65536;  // the group's list is ranked by one wave on 64-bit keys
   float* g_inc = p.cand_inc + (size_t)grp * K;
   float* g_catt = p.cand_att + (size_t)grp * K;
   double* g_ctc = p.cand_ctc + (size_t)grp * K;
@@ -483,56 +502,60 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p
       const int id = ids[b];
       const float4* col = (const float4*)(xu + (size_t)id * p.Tp + t0);
       const float4* f4 = (const float4*)(s_F + ((id == last) ? sm.wp_max : 0));   // Fb follows F
-      Lse a; a.m = LOG0F; a.s = 0.0f;
-      if (!e2) {
+      float inc = LOG0F, pre = LOG0F;
+      {
+        Lse a; a.m = LOG0F; a.s = 0.0f;
+        if (!e2) {
 #pragma unroll
-        for (int it = 0; it < IT; ++it) {
-          const int i = q + it * LPC;
-          if (i < n4) lse_add4(a, x[b][it], f4[i]);
-        }
-        for (int i = q + IT * LPC; i < n4; i += LPC) lse_add4(a, col[i], f4[i]);
-      } else {
-        // eos-run rule armed for g: also the same sum with the last R frames cut off (the running
-        // prefix score at frame T - R), from the same loads
-        Lse ap; ap.m = LOG0F; ap.s = 0.0f;
+          for (int it = 0; it < IT; ++it) {
+            const int i = q + it * LPC;
+            if (i < n4) lse_add4(a, x[b][it], f4[i]);
+          }
+          for (int i = q + IT * LPC; i < n4; i += LPC) lse_add4(a, col[i], f4[i]);
+        } else {
+          Lse ap; ap.m = LOG0F; ap.s = 0.0f;
+          auto upto = [&](const float4 xv, const float4 fv, int tb) {
+            const int tc = T - R;
+            float4 fc;
+            fc.x = tb <= tc ? fv.x : LOG0F; fc.y = tb + 1 <= tc ? fv.y : LOG0F;
+            fc.z = tb + 2 <= tc ? fv.z : LOG0F; fc.w = tb + 3 <= tc ? fv.w : LOG0F;
+            lse_add4(ap, xv, fc);
+          };
 #pragma unroll
-        for (int it = 0; it < IT; ++it) {
-          const int i = q + it * LPC;
-          if (i < n4) { lse_add4(a, x[b][it], f4[i]); lse_add4_upto(ap, x[b][it], f4[i], t0 + 4 * i, T - R); }
+          for (int it = 0; it < IT; ++it) {
+            const int i = q + it * LPC;
+            if (i < n4) { lse_add4(a, x[b][it], f4[i]); upto(x[b][it], f4[i], t0 + 4 * i); }
+          }
+          for (int i = q + IT * LPC; i < n4; i += LPC) {
+            const float4 xv = col[i];
+            lse_add4(a, xv, f4[i]); upto(xv, f4[i], t0 + 4 * i);
+          }
+          pre = lse_finish<LPC>(ap);
         }
-        for (int i = q + IT * LPC; i < n4; i += LPC) {
-          const float4 xv = col[i];
-          lse_add4(a, xv, f4[i]); lse_add4_upto(ap, xv, f4[i], t0 + 4 * i, T - R);
-        }
-        const float pre = lse_finish<LPC>(ap);
-        if (q == 0) { if (smallk) s_pre[c] = pre; else p.cand_pre[(size_t)grp * K + c] = pre; }
+        inc = (W > 0) ? lse_finish<LPC>(a) : LOG0F;
       }
-      const float inc = (W > 0) ? lse_finish<LPC>(a) : LOG0F;
       if (q == 0) {
         const float av = (smallk ? s_av[c] : arow[id]) - row_lse;
         const bool valid = inc > LOG0_CLASS;
         const double ctc = valid ? offr + (double)inc : LOG0D;
         const double J = valid ? lam * ctc + (1.0 - lam) * (double)av + jbase : LOG0D;
-        // small K: scores stay in LDS for the ranking below, the per-candidate arrays in global memory
+        // small K: scores stay in LDS for the ranking below; per-candidate arrays in global memory
         // (read back by ctcbs_peek only) are written from there at the very end, so that no store
         // is pending while columns are still being fetched
-        if (smallk) { s_J[c] = (valid && J == J) ? J : LOG0D; s_inc[c] = inc; s_av[c] = av; s_Jraw[c] = J; }
-        else { g_inc[c] = inc; g_catt[c] = av; g_ctc[c] = ctc; g_joint[c] = J; }
+        if (smallk) {
+          s_J[c] = J; s_inc[c] = inc; s_av[c] = av;
+          s_key[c] = joint_key(J, id & 0xFFFF, valid && J == J);
+          if (e2) s_pre[c] = pre;
+        } else {
+          g_inc[c] = inc; g_catt[c] = av; g_ctc[c] = ctc; g_joint[c] = J;
+          if (e2) p.cand_pre[(size_t)grp * K + c] = pre;
+        }
       }
     }
   }
 
   TRACE_MARK(4);
-  // ---------------- 4. eos, eos-run rule, group list -------------------------------------
-  if (tid == 0) {
-    const float ce = (rs <= T && re >= T) ? canon0(lae(eos_n, eos_b)) : LOG0F;
-    const bool v = ce > LOG0_CLASS;
-    const double ctc = v ? offr + BT + (double)ce : LOG0D;  // phi_T(g) = off' + B_T + stored
-    p.ctc_eos[grp] = ctc;
-    p.joint_eos[grp] = v ? lam * ctc + (1.0 - lam) * (double)(eos_a - row_lse) + jbase : LOG0D;
-    p.win_s[grp] = s; p.win_e[grp] = e;
-    p.grp_cells[grp] = (long long)K * (long long)W;
-  }
+  // ---------------- 4. eos-run rule, group list, outputs -----------------------------------
   int fire = 0;
   if (e2) {
     // Frame T is one of the R frames and there X_T is simply the best full prefix score of the
@@ -571,8 +594,7 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p
 #pragma unroll
         for (int k = 0; k < E2C; ++k) {
           if (k0 + k < R) {
-            const int t = T - R + 1 + k0 + k;
-            acc = lae(acc, ff[t - t0] + xv[k]);
+            acc = lae(acc, ff[T - R + 1 + k0 + k - t0] + xv[k]);
             xmax[k] = fmaxf(xmax[k], canon0(acc));
           }
         }
@@ -602,52 +624,78 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p
     lds_barrier();
     fire = s_nvalid;
     }                                                      // maybe
-    if (tid == 0) p.stopped[grp] = fire;
     lds_barrier();                                         // s_nvalid is reset below
-  } else if (tid == 0) {
-    p.stopped[grp] = 0;
+  }
+  if (tid == 0) {
+    p.stopped[grp] = fire;
+    p.ctc_eos[grp] = s_eos[0]; p.joint_eos[grp] = s_eos[1];
+    p.win_s[grp] = s; p.win_e[grp] = e;
+    p.grp_cells[grp] = (long long)K * (long long)W;
   }
 
   if (smallk) {
-    // rank by (joint desc, token asc)
-    if (tid == 0) s_nvalid = 0;
-    lds_barrier();                                         // s_J complete
-    if (!fire) {
-      const int part = tid & 3;
-      for (int e0 = 0; e0 < K; e0 += BLOCK / 4) {          // four lanes per candidate
-        const int e = e0 + (tid >> 2);
-        const double me = e < K ? s_J[e] : LOG0D;
-        const int mtok = e < K ? s_cid[e] : 0x7fffffff;
-        int rank = 0;
-        for (int c = part; c < K; c += 4) {
-          const double o = s_J[c];
-          rank += (o > me) || (o == me && s_cid[c] < mtok);
-        }
-        rank += __shfl_xor(rank, 1);
-        rank += __shfl_xor(rank, 2);
-        if (part == 0 && e < K && me > (double)LOG0_CLASS) {
-          if (rank < p.Wb) {
-            const size_t o = (size_t)grp * p.Wb + rank;
-            p.grp_J[o] = me; p.grp_ci[o] = e; p.grp_tok[o] = s_cid[e];
-            p.grp_inc[o] = s_inc[e]; p.grp_att[o] = s_av[e];
+    if (wave_rank) {
+      // rank by (joint desc, token asc) on 64-bit keys: one lane of the first wave per candidate
+      lds_barrier();                                       // keys and scores complete; the other waves are done
+      if (tid >= 64) return;
+      const unsigned long long me = tid < K ? s_key[tid] : 0ull;
+      int rank = 0;
+      const ulonglong2* k2 = (const ulonglong2*)s_key;
+      for (int c = 0; c + 1 < K; c += 2) {
+        const ulonglong2 o = k2[c >> 1];
+        rank += (int)(o.x > me) + (int)(o.y > me);
+      }
+      if (K & 1) rank += (int)(s_key[K - 1] > me);
+      const int nv = __popcll(__ballot(me != 0ull));
+      if (!fire && me != 0ull && rank < p.Wb) {
+        const size_t o = (size_t)grp * p.Wb + rank;
+        p.grp_J[o] = s_J[tid]; p.grp_ci[o] = tid; p.grp_tok[o] = s_cid[tid];
+        p.grp_inc[o] = s_inc[tid]; p.grp_att[o] = s_av[tid];
+      }
+      if (tid == 0) p.grp_n[grp] = fire ? 0 : min(nv, p.Wb);
+    } else {
+      // rank by (joint desc, token asc), exact comparison: four lanes per candidate
+      if (tid == 0) s_nvalid = 0;
+      lds_barrier();                                       // scores complete
+      if (!fire) {
+        const int part = tid & 3;
+        for (int e0 = 0; e0 < K; e0 += BLOCK / 4) {
+          const int ee = e0 + (tid >> 2);
+          const bool mv = ee < K && s_key[ee] != 0ull;
+          const double me = mv ? s_J[ee] : LOG0D;
+          const int mtok = ee < K ? s_cid[ee] : 0x7fffffff;
+          int rank = 0;
+          for (int c = part; c < K; c += 4) {
+            const double o = s_key[c] != 0ull ? s_J[c] : LOG0D;
+            rank += (o > me) || (o == me && s_cid[c] < mtok);
           }
-          atomicAdd(&s_nvalid, 1);
+          rank += dpp_i<0xB1, 0xf>(0, rank);               // quad_perm [1,0,3,2]
+          rank += dpp_i<0x4E, 0xf>(0, rank);               // quad_perm [2,3,0,1]
+          if (part == 0 && mv) {
+            if (rank < p.Wb) {
+              const size_t o = (size_t)grp * p.Wb + rank;
+              p.grp_J[o] = me; p.grp_ci[o] = ee; p.grp_tok[o] = s_cid[ee];
+              p.grp_inc[o] = s_inc[ee]; p.grp_att[o] = s_av[ee];
+            }
+            atomicAdd(&s_nvalid, 1);
+          }
         }
       }
+      lds_barrier();
+      if (tid == 0) p.grp_n[grp] = fire ? 0 : min(s_nvalid, p.Wb);
     }
-    lds_barrier();
-    if (tid == 0) p.grp_n[grp] = fire ? 0 : min(s_nvalid, p.Wb);
-    for (int c = tid; c < K; c += BLOCK) {
-      const float inc = s_inc[c];
-      g_cid[c] = s_cid[c]; g_inc[c] = inc; g_catt[c] = s_av[c];
-      g_ctc[c] = inc > LOG0_CLASS ? offr + (double)inc : LOG0D;
-      g_joint[c] = s_Jraw[c];
+    if (p.keep_cand) {
+      for (int c = tid; c < K; c += BLOCK) {
+        const float inc = s_inc[c];
+        g_cid[c] = s_cid[c]; g_inc[c] = inc; g_catt[c] = s_av[c];
+        g_ctc[c] = inc > LOG0_CLASS ? offr + (double)inc : LOG0D;
+        g_joint[c] = s_J[c];
+      }
     }
   }
   TRACE_MARK(5);
   TRACE_FLUSH(p, grp);
 }
-
 // Group list for large candidate sets (K > block size): Wb rounds of a block-wide argmax
 // over the joint scores in global memory.  One work-group per (utterance, beam slot).
 template <int BLOCK>
@@ -657,7 +705,7 @@ __global__ __launch_bounds__(BLOCK) void k_group_top(Params p, int cur) {
   __shared__ int s_pick[MAX_BEAM];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int grp = blockIdx.x, u = grp / p.Wb, K = p.K;
-  if (p.finished[u] || !p.h_live[cur][grp]) return;      // k_score already wrote grp_n = 0
+  if (p.finished[u] || !p.rec[cur][grp].live) return;      // k_score already wrote grp_n = 0
   if (p.stopped[grp]) { if (tid == 0) p.grp_n[grp] = 0; return; }
   const double* J = p.cand_joint + (size_t)grp * K;
   const int32_t* ids = p.cand_id + (size_t)grp * K;       // equal scores: smaller token id first
@@ -707,7 +755,7 @@ __global__ __launch_bounds__(BLOCK) void k_group_top_regs(Params p, int cur) {
   __shared__ unsigned long long s_k[2][NW];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int grp = blockIdx.x, u = grp / p.Wb, K = p.K;
-  if (p.finished[u] || !p.h_live[cur][grp]) return;      // the score kernel already wrote grp_n = 0
+  if (p.finished[u] || !p.rec[cur][grp].live) return;      // the score kernel already wrote grp_n = 0
   if (p.stopped[grp]) { if (tid == 0) p.grp_n[grp] = 0; return; }
   const double* J = p.cand_joint + (size_t)grp * K;
   unsigned long long key[EPT];

@@ -45,17 +45,18 @@ __global__ __launch_bounds__(BLOCK) void k_score_dense(Params p, const float* __
   __syncthreads();
   if (tid < Wb) {
     const size_t h = h0 + tid;
-    const int live = !fin && p.h_live[cur][h] != 0;
-    const int tau = p.h_tau[cur][h], tau_end = p.h_tau_end[cur][h];
+    const HypRec r = p.rec[cur][h];
+    const int live = !fin && r.live != 0;
+    const int tau = r.tau, tau_end = r.tau_end;
     int s = l > 1 ? l : 1, e = T;
     if (p.win_m1 >= 0) s = max(s, tau - p.win_m1);
     if (p.win_m2 >= 0) e = min(e, tau_end + p.win_m2);
     // (a slot that never held a hypothesis has a record nobody wrote: nothing of it may steer an access)
-    const int ref = live ? checked(p, p.h_ref[cur][h], 0, T, ERR_TIME_INDEX) : 0;
-    q_live[tid] = live; q_last[tid] = p.h_last[cur][h]; q_s[tid] = s; q_e[tid] = e;
-    q_rs[tid] = p.h_rs[cur][h]; q_re[tid] = p.h_re[cur][h]; q_ref[tid] = ref;
-    q_offr[tid] = p.h_off[cur][h] + Bu[ref];
-    q_jbase[tid] = (1.0 - p.lambda) * p.h_att[cur][h] + p.beta * (double)l;
+    const int ref = live ? checked(p, r.ref, 0, T, ERR_TIME_INDEX) : 0;
+    q_live[tid] = live; q_last[tid] = r.last; q_s[tid] = s; q_e[tid] = e;
+    q_rs[tid] = r.rs; q_re[tid] = r.re; q_ref[tid] = ref;
+    q_offr[tid] = r.off + Bu[ref];
+    q_jbase[tid] = (1.0 - p.lambda) * r.att + p.beta * (double)l;
     if (live && e >= s) { atomicMin(&s_lo, s); atomicMax(&s_hi, e); }
     if (chunk == 0 && !live) {
       p.grp_n[h] = 0; p.win_s[h] = 0; p.win_e[h] = -1; p.stopped[h] = 0;

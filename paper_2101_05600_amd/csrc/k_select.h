@@ -81,7 +81,7 @@ struct SurvivorIn {
 // FPL consecutive frames per lane, 64 * FPL frames per pass.
 template <int FPL>
 __device__ __forceinline__ void wave_survivor_fpl(const Params& p, int u, int n, int cur, const SurvivorIn& in,
-                                                  int& arg_n, int& arg_b, float& delta_out) {
+                                                  int& arg_n, int& arg_b, float& delta_out, double& bref_out) {
   const int lane = threadIdx.x & 63;
   const size_t h0 = (size_t)u * p.Wb;
   const size_t hp = h0 + checked(p, in.par, 0, p.Wb - 1, ERR_LIST_ENTRY);
@@ -98,6 +98,7 @@ __device__ __forceinline__ void wave_survivor_fpl(const Params& p, int u, int n,
   const double Bnew = Bu[checked(p, in.ptau, 0, T, ERR_TIME_INDEX)];   // the child's reference frame is the parent's tau
   const float delta = in.inc + (float)(Bu[checked(p, in.pref, 0, T, ERR_TIME_INDEX)] - Bnew);
   delta_out = delta;
+  bref_out = Bnew;
   const bool rep = (in.tok == in.plast);
   const int lo = max(s, in.ptau);
   float carry_n = LOG0F, carry_b = LOG0F;
@@ -173,11 +174,11 @@ __device__ __forceinline__ void wave_survivor_fpl(const Params& p, int u, int n,
 // windows of up to 128 frames: two frames per lane, one pass; up to 256: four per lane (a pass costs
 // about 1.4 times as much and covers twice as many frames); longer ones: eight per lane
 __device__ __forceinline__ void wave_survivor(const Params& p, int u, int n, int cur, const SurvivorIn& in,
-                                              int& arg_n, int& arg_b, float& delta_out) {
+                                              int& arg_n, int& arg_b, float& delta_out, double& bref_out) {
   const int W = in.en - in.s + 1;
-  if (W <= 128) wave_survivor_fpl<2>(p, u, n, cur, in, arg_n, arg_b, delta_out);
-  else if (W <= 256) wave_survivor_fpl<4>(p, u, n, cur, in, arg_n, arg_b, delta_out);
-  else wave_survivor_fpl<8>(p, u, n, cur, in, arg_n, arg_b, delta_out);
+  if (W <= 128) wave_survivor_fpl<2>(p, u, n, cur, in, arg_n, arg_b, delta_out, bref_out);
+  else if (W <= 256) wave_survivor_fpl<4>(p, u, n, cur, in, arg_n, arg_b, delta_out, bref_out);
+  else wave_survivor_fpl<8>(p, u, n, cur, in, arg_n, arg_b, delta_out, bref_out);
 }
 
 // How many of the keys s_k2[0 .. 2 * quads) (four per quad, zero padding at the end) exceed `me`,
@@ -319,6 +320,7 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
   __shared__ int s_fin;
   __shared__ int s_ntau[MAX_BEAM], s_ntau_end[MAX_BEAM];   // time indices of the new hypotheses
   __shared__ float s_delta[MAX_BEAM];                      // by how much each new hypothesis was re-based
+  __shared__ double s_bref[MAX_BEAM];                      // B at each new hypothesis's reference frame
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int u = blockIdx.x, Wb = p.Wb;
@@ -330,12 +332,13 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
   // ---- round 1: every independent load ------------------------------------------------------
   if (tid < Wb) {
     const size_t h = h0 + tid;
-    o_live[tid] = p.h_live[cur][h]; o_n[tid] = p.grp_n[h]; o_stp[tid] = p.stopped[h];
-    o_tau[tid] = p.h_tau[cur][h]; o_tau_end[tid] = p.h_tau_end[cur][h];
-    o_rs[tid] = p.h_rs[cur][h]; o_re[tid] = p.h_re[cur][h]; o_last[tid] = p.h_last[cur][h];
-    o_ws[tid] = p.win_s[h]; o_we[tid] = p.win_e[h]; o_ref[tid] = p.h_ref[cur][h];
+    const HypRec r = p.rec[cur][h];
+    o_live[tid] = r.live; o_n[tid] = p.grp_n[h]; o_stp[tid] = p.stopped[h];
+    o_tau[tid] = r.tau; o_tau_end[tid] = r.tau_end;
+    o_rs[tid] = r.rs; o_re[tid] = r.re; o_last[tid] = r.last;
+    o_ws[tid] = p.win_s[h]; o_we[tid] = p.win_e[h]; o_ref[tid] = r.ref;
     o_cells[tid] = p.grp_cells[h];
-    o_je[tid] = p.joint_eos[h]; o_hatt[tid] = p.h_att[cur][h]; o_off[tid] = p.h_off[cur][h];
+    o_je[tid] = p.joint_eos[h]; o_hatt[tid] = r.att; o_off[tid] = r.off;
   }
   const int T = p.lens[u];
   const int lmax_u = p.lmax[u];
@@ -425,12 +428,12 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
     in.ptau = o_tau[par]; in.ptau_end = o_tau_end[par]; in.plast = o_last[par]; in.pref = o_ref[par];
     int arg_n, arg_b;
     float delta;
-    wave_survivor(p, u, n, cur, in, arg_n, arg_b, delta);
+    double bref;
+    wave_survivor(p, u, n, cur, in, arg_n, arg_b, delta, bref);
     if (lane == 0) {
-      p.h_tau[nxt][h0 + n] = arg_n; p.h_tau_end[nxt][h0 + n] = arg_b;
       p.out_tau[h0 + n] = arg_n; p.out_tau_end[h0 + n] = arg_b;
       p.trie_tau[trie_l + n] = arg_n;
-      s_ntau[n] = arg_n; s_ntau_end[n] = arg_b; s_delta[n] = delta;
+      s_ntau[n] = arg_n; s_ntau_end[n] = arg_b; s_delta[n] = delta; s_bref[n] = bref;
     }
   }
   lds_barrier();                       // (the survivors' state stores stay in flight)
@@ -443,13 +446,14 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
       p.out_parent[h] = par; p.out_token[h] = tok; p.out_score[h] = (float)s_J[e];
       p.out_live[h] = fin ? 0 : 1;
       p.trie_parent[trie_l + n] = par; p.trie_token[trie_l + n] = tok;
-      p.h_live[nxt][h] = fin ? 0 : 1;
-      p.h_last[nxt][h] = tok;
-      p.h_rs[nxt][h] = o_ws[par]; p.h_re[nxt][h] = o_we[par];
-      p.h_off[nxt][h] = o_off[par] + (double)s_delta[n];
-      p.h_ref[nxt][h] = o_tau[par];
-      p.h_att[nxt][h] = o_hatt[par] + (double)s_att[e];
-      p.h_joint[nxt][h] = s_J[e];
+      HypRec r;
+      r.live = fin ? 0 : 1; r.last = tok; r.rs = o_ws[par]; r.re = o_we[par];
+      r.tau = s_ntau[n]; r.tau_end = s_ntau_end[n]; r.ref = o_tau[par]; r.pad = 0;
+      r.off = o_off[par] + (double)s_delta[n];
+      r.att = o_hatt[par] + (double)s_att[e];
+      r.joint = s_J[e];
+      r.bref = s_bref[n];
+      p.rec[nxt][h] = r;
       if (p.win_union && !fin) {                 // this hypothesis's share of the next step's window
         atomicMin(&p.union_win[2 * ((l + 1) & 1)], s_ntau[n]);
         atomicMax(&p.union_win[2 * ((l + 1) & 1) + 1], min(s_ntau_end[n] + p.win_m2, T));
@@ -458,7 +462,7 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
       p.out_parent[h] = -1; p.out_token[h] = -1; p.out_score[h] = LOG0F; p.out_live[h] = 0;
       p.out_tau[h] = 0; p.out_tau_end[h] = 0;
       p.trie_parent[trie_l + n] = -1; p.trie_token[trie_l + n] = -1; p.trie_tau[trie_l + n] = 0;
-      p.h_live[nxt][h] = 0;
+      p.rec[nxt][h].live = 0;
     }
   }
 
@@ -507,12 +511,13 @@ __global__ __launch_bounds__(BLOCK) void k_select_split(Params p, int l, int cur
   // ---- round 1: every independent load ------------------------------------------------------
   if (tid < Wb) {
     const size_t h = h0 + tid;
-    o_live[tid] = p.h_live[cur][h]; o_n[tid] = p.grp_n[h]; o_stp[tid] = p.stopped[h];
-    o_tau[tid] = p.h_tau[cur][h]; o_tau_end[tid] = p.h_tau_end[cur][h];
-    o_rs[tid] = p.h_rs[cur][h]; o_re[tid] = p.h_re[cur][h]; o_last[tid] = p.h_last[cur][h];
-    o_ws[tid] = p.win_s[h]; o_we[tid] = p.win_e[h]; o_ref[tid] = p.h_ref[cur][h];
+    const HypRec r = p.rec[cur][h];
+    o_live[tid] = r.live; o_n[tid] = p.grp_n[h]; o_stp[tid] = p.stopped[h];
+    o_tau[tid] = r.tau; o_tau_end[tid] = r.tau_end;
+    o_rs[tid] = r.rs; o_re[tid] = r.re; o_last[tid] = r.last;
+    o_ws[tid] = p.win_s[h]; o_we[tid] = p.win_e[h]; o_ref[tid] = r.ref;
     o_cells[tid] = p.grp_cells[h];
-    o_je[tid] = p.joint_eos[h]; o_hatt[tid] = p.h_att[cur][h]; o_off[tid] = p.h_off[cur][h];
+    o_je[tid] = p.joint_eos[h]; o_hatt[tid] = r.att; o_off[tid] = r.off;
   }
   const int T = p.lens[u];
   const int lmax_u = p.lmax[u];
@@ -588,19 +593,20 @@ __global__ __launch_bounds__(BLOCK) void k_select_split(Params p, int l, int cur
       in.ptau = o_tau[par]; in.ptau_end = o_tau_end[par]; in.plast = o_last[par]; in.pref = o_ref[par];
       int arg_n, arg_b;
       float delta;
-      wave_survivor(p, u, n, cur, in, arg_n, arg_b, delta);
+      double bref;
+      wave_survivor(p, u, n, cur, in, arg_n, arg_b, delta, bref);
       if (lane == 0) {
-        p.h_tau[nxt][h] = arg_n; p.h_tau_end[nxt][h] = arg_b;
         p.out_tau[h] = arg_n; p.out_tau_end[h] = arg_b;
         p.trie_tau[trie_l + n] = arg_n;
         p.out_parent[h] = par; p.out_token[h] = in.tok; p.out_score[h] = (float)s_J[e];
         p.trie_parent[trie_l + n] = par; p.trie_token[trie_l + n] = in.tok;
-        p.h_last[nxt][h] = in.tok;
-        p.h_rs[nxt][h] = in.s; p.h_re[nxt][h] = in.en;
-        p.h_off[nxt][h] = o_off[par] + (double)delta;
-        p.h_ref[nxt][h] = in.ptau;
-        p.h_att[nxt][h] = o_hatt[par] + (double)s_att[e];
-        p.h_joint[nxt][h] = s_J[e];
+        // (the record's live flag belongs to the utterance's lead work-group, see below)
+        HypRec* r = p.rec[nxt] + h;
+        r->last = in.tok; r->rs = in.s; r->re = in.en; r->tau = arg_n; r->tau_end = arg_b; r->ref = in.ptau;
+        r->off = o_off[par] + (double)delta;
+        r->att = o_hatt[par] + (double)s_att[e];
+        r->joint = s_J[e];
+        r->bref = bref;
       }
     } else if (lane == 0) {
       p.out_parent[h] = -1; p.out_token[h] = -1; p.out_score[h] = LOG0F;
@@ -618,7 +624,7 @@ __global__ __launch_bounds__(BLOCK) void k_select_split(Params p, int l, int cur
     if (lane < Wb) {
       const int lv = (lane < n_new && !fin) ? 1 : 0;
       p.out_live[h0 + lane] = (uint8_t)lv;
-      p.h_live[nxt][h0 + lane] = lv;
+      p.rec[nxt][h0 + lane].live = lv;
     }
   }
   if (lead) TRACE_POINT(p, u, 13);

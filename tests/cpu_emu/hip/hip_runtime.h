@@ -52,7 +52,7 @@ inline int emu_poison_byte() {
   return b;
 }
 inline hipError_t hipMalloc(void** p, size_t n) {
-  *p = malloc(n ? n : 1);
+  if (posix_memalign(p, 256, n ? n : 1) != 0) *p = nullptr;   // (hipMalloc returns 256-byte aligned memory)
   if (*p) memset(*p, emu_poison_byte(), n ? n : 1);
   return *p ? hipSuccess : hipErrorOutOfMemory;
 }
@@ -261,6 +261,17 @@ inline unsigned long long __ballot(int pred) {
   return m;
 }
 inline int __builtin_amdgcn_readlane(int v, int lane) { return emu::from_lane(v, lane); }
+// bits of a 64-bit lane mask (given as its two halves) set below the calling lane, plus `add`
+inline unsigned __builtin_amdgcn_mbcnt_lo(unsigned m, unsigned add) {
+  const int l = emu::self().lane;
+  const unsigned below = l >= 32 ? 0xffffffffu : ((1u << l) - 1u);
+  return (unsigned)__builtin_popcount(m & below) + add;
+}
+inline unsigned __builtin_amdgcn_mbcnt_hi(unsigned m, unsigned add) {
+  const int l = emu::self().lane;
+  const unsigned below = l <= 32 ? 0u : ((1u << (l - 32)) - 1u);
+  return (unsigned)__builtin_popcount(m & below) + add;
+}
 // DPP controls of GFX9 (all lanes active, bank mask 0xf): quad_perm, row_shl/shr/ror, wave_shr:1,
 // row_mirror, row_bcast15, row_bcast31; a lane without a source, or in a row that the row mask
 // leaves out, keeps `old`

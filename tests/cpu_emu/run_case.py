@@ -32,6 +32,13 @@ CASES = {
     # fewer ids than beam slots: most slots never hold a hypothesis, their records are never written
     "all_candidates_few_ids": (dict(n_utt=2, vocab=6, beam=6, cand_k=0, win_m1=-1, win_m2=-1, end_flags=3,
                                     max_len_ratio=0.4), [9, 7]),
+    # a vocabulary large enough for the register-resident candidate selection to succeed (pivot, per-wave
+    # stretches of the short list, ranking), eos-run rule armed, list ranked by one wave
+    "pivot": (dict(n_utt=1, vocab=2048, beam=2, cand_k=12, win_m1=6, win_m2=6, end_flags=7, eos_run=3,
+                   max_len_ratio=0.3), [16]),
+    # more than 64 candidates per hypothesis: the group's list is ranked by the whole work-group
+    "pivot_k80": (dict(n_utt=1, vocab=1024, beam=2, cand_k=80, win_m1=-1, win_m2=-1, end_flags=3,
+                       max_len_ratio=0.3), [12]),
     # logits in, odd vocabulary (radix selection), one candidate per hypothesis
     "logits_odd_vocab": (dict(n_utt=1, vocab=33, beam=2, cand_k=1, win_m1=3, win_m2=8, end_flags=2, att_is_logits=1,
                               max_len_ratio=0.4), [13]),

@@ -74,7 +74,8 @@ def runs(tmp_path_factory):
     asan, tsan = _runtime("libasan.so"), _runtime("libtsan.so")
     plan = {
         "asan": (asan, ASAN_ENV, dict(sanitize=True),
-                 ["windowed", "batch_window", "all_candidates", "all_candidates_few_ids", "logits_odd_vocab"]),
+                 ["windowed", "batch_window", "all_candidates", "all_candidates_few_ids", "logits_odd_vocab",
+                  "pivot", "pivot_k80"]),
         # executor: the job queue with two host threads on two handles
         "tsan": (tsan, TSAN_ENV, dict(sanitize="thread"), ["windowed", "batch_window", "executor"]),
         "tsan_planted": (tsan, TSAN_ENV, dict(sanitize="thread", plant=PLANT), ["windowed"]),
@@ -104,7 +105,7 @@ def test_kernels_under_address_and_ub_sanitizers(runs):
     r, out = _result(runs, "asan")
     assert r.returncode == 0, out[-4000:]
     assert "ERROR: AddressSanitizer" not in out and "runtime error:" not in out, out[-4000:]
-    assert out.count("emu ok") == 5, out[-2000:]
+    assert out.count("emu ok") == 7, out[-2000:]
 
 
 def test_kernels_under_thread_sanitizer(runs):

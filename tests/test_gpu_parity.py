@@ -550,3 +550,83 @@ def test_executor_error_paths():
     finally:
         for d in decs:
             d.close()
+
+
+def _decode_outputs(w, ctc, lens, keep, att_offset=0):
+    """Free-running decode (no oracle): every step's outputs, and the result.  att_offset: the attention
+    buffer handed to ctcbs_step starts that many floats after a 16-byte boundary."""
+    import torch
+    import paper_2101_05600_amd as m
+    U, Wb, V = len(lens), w["beam"], w["vocab"]
+    cfg = m.make_config(n_utt=U, t_max=ctc.shape[1], keep_candidates=keep,
+                        **{k: v for k, v in w.items() if k not in ("n_utt", "keep_candidates")})
+    d_ctc = torch.from_numpy(np.ascontiguousarray(ctc)).cuda()
+    h = m.ctcbs_create(cfg, d_ctc, lens)
+    out = m.StepOut()
+    buf = torch.empty(U * Wb * V + 8, dtype=torch.float32, device="cuda")
+    d_att = buf[att_offset:att_offset + U * Wb * V].view(U, Wb, V)
+    assert d_att.data_ptr() % 16 == (4 * att_offset) % 16
+    steps = []
+    try:
+        basis = gen.prefix_hash([])
+        hashes = [[basis] * Wb for _ in range(U)]
+        live = np.zeros((U, Wb), bool)
+        live[:, 0] = True
+        for step in range(1, 10000):
+            att = host_att(w, step, hashes, live, U)
+            d_att.copy_(torch.from_numpy(att))
+            if m.ctcbs_step(h, d_att.data_ptr(), out) == m.DONE:
+                break
+            g = lambda p, shape, dt: m.view(p, shape, dt).cpu().numpy()
+            o = dict(parent=g(out.d_parent, (U, Wb), np.int32), token=g(out.d_token, (U, Wb), np.int32),
+                     score=g(out.d_score, (U, Wb), np.float32), live=g(out.d_live, (U, Wb), np.uint8),
+                     finished=g(out.d_finished, (U,), np.uint8), tau=g(out.d_tau, (U, Wb), np.int32),
+                     eos_added=g(out.d_eos_added, (U, Wb), np.uint8), stopped=g(out.d_stopped, (U, Wb), np.uint8))
+            steps.append(o)
+            new_hashes = [[basis] * Wb for _ in range(U)]
+            for u in range(U):
+                for n in range(Wb):
+                    if o["live"][u, n]:
+                        new_hashes[u][n] = gen.prefix_hash_extend(hashes[u][o["parent"][u, n]], o["token"][u, n])
+            hashes, live = new_hashes, o["live"].astype(bool)
+            if o["finished"].all():
+                break
+        peek_rc = m.lib().ctcbs_peek(h, m.PEEK_CAND_ID, None, 0, None)
+        res = m.ctcbs_finalize(h, U, 400)
+    finally:
+        m.ctcbs_destroy(h)
+    return steps, res, peek_rc
+
+
+def test_keep_candidates_off_gives_the_same_steps_and_results():
+    """The per-candidate arrays that ctcbs_peek reads are a create-time option; without them the step
+    outputs and the results are bit-identical (and peeking at them is refused)."""
+    import paper_2101_05600_amd as m
+    w = small("cfg1", n_utt=4, t_lo=60, t_hi=170, vocab=1200, beam=6, cand_k=24, win_m1=15, win_m2=20,
+              end_flags=7, eos_run=5)
+    lens, ctc = make_inputs(w)
+    s1, r1, rc1 = _decode_outputs(w, ctc, lens, keep=1)
+    s0, r0, rc0 = _decode_outputs(w, ctc, lens, keep=0)
+    assert rc1 == m.OK and rc0 == m.ESTATE
+    assert len(s1) == len(s0) and len(s1) > 10
+    for a, b in zip(s1, s0):
+        for k in a:
+            assert np.array_equal(a[k], b[k]), k
+    for a, b in zip(r1, r0):
+        assert (a is None and b is None) or np.array_equal(a, b)
+
+
+def test_attention_rows_off_a_16_byte_boundary():
+    """An attention buffer that does not start on a 16-byte boundary takes the slower candidate
+    selection and gives the same decode."""
+    w = small("cfg1", n_utt=3, t_lo=50, t_hi=120, vocab=1200, beam=4, cand_k=16, win_m1=15, win_m2=20,
+              end_flags=7, eos_run=5)
+    lens, ctc = make_inputs(w)
+    s_al, r_al, _ = _decode_outputs(w, ctc, lens, keep=0, att_offset=0)
+    s_un, r_un, _ = _decode_outputs(w, ctc, lens, keep=0, att_offset=1)
+    assert len(s_al) == len(s_un) and len(s_al) > 10
+    for a, b in zip(s_al, s_un):
+        for k in a:
+            assert np.array_equal(a[k], b[k]), k
+    for a, b in zip(r_al, r_un):
+        assert (a is None and b is None) or np.array_equal(a, b)
