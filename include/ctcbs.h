@@ -159,6 +159,26 @@ int ctcbs_reset(ctcbs_t* h, const float* d_ctc_logp, const int32_t* h_lens);
  */
 int ctcbs_step(ctcbs_t* h, const float* d_att_logp, ctcbs_step_out_t* out);
 
+/*
+ * ctcbs_step for callers that cannot allocate device memory and want a step whose working set
+ * beyond the handle's state lies at a fixed place: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same outputs and return
+ * codes as ctcbs_step, bit for bit; the two may be mixed freely on one handle.  The arrays that
+ * carry a step's intermediate values from the score kernel to the select kernel (windows, eos
+ * scores, the groups' best-first lists, stop flags, work counts) lie in a fixed 4 MiB array inside
+ * the library's image (one copy per GPU, held until the process ends) instead of the handle's own
+ * memory.  The call allocates nothing, on the host or on the device, and enqueues no memset.
+ * Limits: the device the handle was created on must be current (else CTCBS_ESTATE); at most 256
+ * candidates per hypothesis and not every id a candidate, and
+ * 40*U*Wb + 24*U*Wb*Wb bytes (each array rounded up to 256) within the 4 MiB (else CTCBS_EINVAL:
+ * e.g. U = 256 at beam 20 fits, U = 2048 at beam 10 does not).
+ * Every call on a GPU uses that GPU's one array, whatever the handle: steps of different handles
+ * (or streams) that overlap in time on one GPU race on it.  Callers that keep several batches in
+ * flight use ctcbs_step.  ctcbs_peek of windows and eos scores reads the arrays of the handle's
+ * last step, wherever they lie; with this call they hold what the GPU's last call left there.
+ */
+int ctcbs_step_static(ctcbs_t* h, const float* d_att_logp, ctcbs_step_out_t* out);
+
 /* Synchronise and read how many utterances have finished (Algorithm 2's loop exit test). */
 int ctcbs_poll(ctcbs_t* h, int32_t* n_finished);
 

@@ -24,7 +24,7 @@ PEEK_CTC_EOS, PEEK_JOINT_EOS, PEEK_N_CAND = 6, 7, 8
 HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
-EXPORTS = ["ctcbs_create", "ctcbs_step", "ctcbs_poll", "ctcbs_finalize", "ctcbs_stats", "ctcbs_peek",
+EXPORTS = ["ctcbs_create", "ctcbs_step", "ctcbs_step_static", "ctcbs_poll", "ctcbs_finalize", "ctcbs_stats", "ctcbs_peek",
            "ctcbs_destroy", "ctcbs_strerror", "ctcbs_last_hip_error", "ctcbs_profile",
            "ctcbs_profile_read", "ctcbs_reset", "ctcbs_hard_segments", "ctcbs_merge_pieces",
            "ctcbs_plan_batches", "ctcbs_run_many", "ctcbs_att_replay", "ctcbs_run_queue"]
@@ -96,6 +96,8 @@ def lib():
         L.ctcbs_reset.argtypes = [vp, vp, vp]
         L.ctcbs_step.restype = i32
         L.ctcbs_step.argtypes = [vp, vp, ctypes.POINTER(StepOut)]
+        L.ctcbs_step_static.restype = i32
+        L.ctcbs_step_static.argtypes = [vp, vp, ctypes.POINTER(StepOut)]
         L.ctcbs_poll.restype = i32
         L.ctcbs_poll.argtypes = [vp, ctypes.POINTER(i32)]
         L.ctcbs_finalize.restype = i32
@@ -190,6 +192,14 @@ def ctcbs_reset(handle, d_ctc_logp, h_lens):
 def ctcbs_step(handle, d_att_logp, out: StepOut = None):
     """-> OK or DONE.  d_att_logp: device fp32 [U][Wb][V]."""
     rc = lib().ctcbs_step(handle, _ptr(d_att_logp), ctypes.byref(out) if out is not None else None)
+    if rc < 0:
+        raise CtcbsError(rc)
+    return rc
+
+
+def ctcbs_step_static(handle, d_att_logp, out: StepOut = None):
+    """ctcbs_step with its per-step scratch in the library's fixed array (allocates nothing)."""
+    rc = lib().ctcbs_step_static(handle, _ptr(d_att_logp), ctypes.byref(out) if out is not None else None)
     if rc < 0:
         raise CtcbsError(rc)
     return rc

@@ -29,6 +29,7 @@ static thread_local int g_last_hip = 0;
 struct ctcbs {
   ctcbs_config_t cfg;
   Params p;
+  Params p_step;       // the parameter block of the last step enqueued
   ScoreSmem sm;
   hipStream_t stream;
   int device;          // the device the handle lives on (current at creation)
@@ -327,29 +328,31 @@ static hipError_t allow_lds(const void* kernel, size_t bytes) {
 }
 
 template <int BLOCK, int LPC, int CB, int IT>
-static hipError_t launch_score(ctcbs* h, const float* att, int l) {
+static hipError_t launch_score(ctcbs* h, const Params& p, const float* att, int l) {
   hipError_t ea = allow_lds((const void*)k_score<BLOCK, LPC, CB, IT>, h->score_smem_bytes);
   if (ea != hipSuccess) return ea;
   // attention rows that do not start on 16-byte boundaries cannot be loaded as float4: the candidate
   // selection then reads them element by element (slower, equivalent)
-  const int flags = (((uintptr_t)att & 15) == 0 && h->p.V % 4 == 0) ? 1 : 0;
-  hipLaunchKernelGGL((k_score<BLOCK, LPC, CB, IT>), dim3(h->p.Wb, h->p.U), dim3(BLOCK), h->score_smem_bytes,
-                     h->stream, h->p, h->sm, att, l, h->cur, flags);
+  const int flags = (((uintptr_t)att & 15) == 0 && p.V % 4 == 0) ? 1 : 0;
+  hipLaunchKernelGGL((k_score<BLOCK, LPC, CB, IT>), dim3(p.Wb, p.U), dim3(BLOCK), h->score_smem_bytes,
+                     h->stream, p, h->sm, att, l, h->cur, flags);
   return hipGetLastError();
 }
 
 template <int NIT>
-static hipError_t launch_dense(ctcbs* h, const float* att, int l) {
+static hipError_t launch_dense(ctcbs* h, const Params& p, const float* att, int l) {
   hipError_t ea = allow_lds((const void*)k_score_dense<1024, NIT>, h->dense_smem_bytes);
   if (ea != hipSuccess) return ea;
-  hipLaunchKernelGGL((k_score_dense<1024, NIT>), dim3(h->p.U * h->dense_nch), dim3(1024), h->dense_smem_bytes,
-                     h->stream, h->p, att, l, h->cur, h->dense_nch);
+  hipLaunchKernelGGL((k_score_dense<1024, NIT>), dim3(p.U * h->dense_nch), dim3(1024), h->dense_smem_bytes,
+                     h->stream, p, att, l, h->cur, h->dense_nch);
   return hipGetLastError();
 }
 
-extern "C" int ctcbs_step(ctcbs_t* h, const float* d_att_logp, ctcbs_step_out_t* out) {
+// One step with the kernels working on `p`: the handle's own parameter block, or a copy of it whose
+// per-step scratch arrays lie elsewhere (ctcbs_step_static).
+static int step_impl(ctcbs_t* h, const Params& p, const float* d_att_logp, ctcbs_step_out_t* out) {
   if (!h || !d_att_logp) return CTCBS_EINVAL;
-  if (h->known_finished >= h->p.U || h->step >= h->l_cap) return CTCBS_DONE;
+  if (h->known_finished >= p.U || h->step >= h->l_cap) return CTCBS_DONE;
   const int l = h->step + 1;
   hipEvent_t* ev = nullptr;
   if (h->profiling && h->ev_used + 3 <= h->events.size()) {
@@ -357,27 +360,28 @@ extern "C" int ctcbs_step(ctcbs_t* h, const float* d_att_logp, ctcbs_step_out_t*
     h->ev_used += 3;
     HIPCHK(hipEventRecord(ev[0], h->stream));
   }
-  // 16 lanes x 2 float4 per candidate cover windows of up to 128 frames without a second
-  // trip to memory; unrestricted windows use whole waves, 4 float4 (1024 frames) in flight
+  // 16 lanes x 2 float4 per candidate cover windows of up to 128 frames without a second trip to
+  // memory, 16 lanes x 4 float4 wider windows and whole utterances of up to 512 frames; whole-utterance
+  // windows beyond that use whole waves, 4 float4 (1024 frames) in flight (see create_impl)
   hipError_t e;
   switch (h->dense_nit) {                 // every id a candidate: one work-group serves all beam slots
-    case 1: e = launch_dense<1>(h, d_att_logp, l); break;
-    case 2: e = launch_dense<2>(h, d_att_logp, l); break;
-    case 4: e = launch_dense<4>(h, d_att_logp, l); break;
-    case 6: e = launch_dense<6>(h, d_att_logp, l); break;
-    case 8: e = launch_dense<8>(h, d_att_logp, l); break;
+    case 1: e = launch_dense<1>(h, p, d_att_logp, l); break;
+    case 2: e = launch_dense<2>(h, p, d_att_logp, l); break;
+    case 4: e = launch_dense<4>(h, p, d_att_logp, l); break;
+    case 6: e = launch_dense<6>(h, p, d_att_logp, l); break;
+    case 8: e = launch_dense<8>(h, p, d_att_logp, l); break;
     default:
-      e = (h->score_lpc == 16) ? (h->score_wide ? launch_score<256, 16, 2, 4>(h, d_att_logp, l)
-                                                : launch_score<256, 16, 3, 2>(h, d_att_logp, l))
-                               : launch_score<256, 64, 2, 4>(h, d_att_logp, l);
+      e = (h->score_lpc == 16) ? (h->score_wide ? launch_score<256, 16, 2, 4>(h, p, d_att_logp, l)
+                                                : launch_score<256, 16, 3, 2>(h, p, d_att_logp, l))
+                               : launch_score<256, 64, 2, 4>(h, p, d_att_logp, l);
   }
   HIPCHK(e);
   if (ev) HIPCHK(hipEventRecord(ev[1], h->stream));       // (the list builder below counts as selection)
-  if (h->dense_nit || h->p.K > h->score_block) {
-    if (h->p.K <= 1024 * 8)
-      hipLaunchKernelGGL((k_group_top_regs<1024, 8>), dim3(h->p.U * h->p.Wb), dim3(1024), 0, h->stream, h->p, h->cur);
+  if (h->dense_nit || p.K > h->score_block) {
+    if (p.K <= 1024 * 8)
+      hipLaunchKernelGGL((k_group_top_regs<1024, 8>), dim3(p.U * p.Wb), dim3(1024), 0, h->stream, p, h->cur);
     else
-      hipLaunchKernelGGL((k_group_top<256>), dim3(h->p.U * h->p.Wb), dim3(256), 0, h->stream, h->p, h->cur);
+      hipLaunchKernelGGL((k_group_top<256>), dim3(p.U * p.Wb), dim3(256), 0, h->stream, p, h->cur);
     HIPCHK(hipGetLastError());
   }
   // Small batches leave most compute units idle in the one-work-group-per-utterance form: there the
@@ -385,19 +389,20 @@ extern "C" int ctcbs_step(ctcbs_t* h, const float* d_att_logp, ctcbs_step_out_t*
   // faster (measured: U=64 and U=128 at beam 10).  Large batches fill the chip either way and the
   // Wb-fold repeated ranking only costs (U=256 at beam 20: three times slower).  The batch-union
   // window needs the utterance's hypotheses in one place.
-  const bool split = !h->p.win_union && h->p.U * h->p.Wb <= 2048;
-  const size_t split_lds = (size_t)28 * h->p.Wb * h->p.Wb + 64;
+  const bool split = !p.win_union && p.U * p.Wb <= 2048;
+  const size_t split_lds = (size_t)28 * p.Wb * p.Wb + 64;
   if (split) {
-    hipLaunchKernelGGL((k_select_split<256>), dim3(h->p.U * h->p.Wb), dim3(256), split_lds, h->stream, h->p, l, h->cur);
+    hipLaunchKernelGGL((k_select_split<256>), dim3(p.U * p.Wb), dim3(256), split_lds, h->stream, p, l, h->cur);
   } else switch (h->select_block) {
-    case 256: hipLaunchKernelGGL((k_select<256>), dim3(h->p.U), dim3(256), 0, h->stream, h->p, l, h->cur); break;
-    case 512: hipLaunchKernelGGL((k_select<512>), dim3(h->p.U), dim3(512), 0, h->stream, h->p, l, h->cur); break;
-    default: hipLaunchKernelGGL((k_select<1024>), dim3(h->p.U), dim3(1024), 0, h->stream, h->p, l, h->cur); break;
+    case 256: hipLaunchKernelGGL((k_select<256>), dim3(p.U), dim3(256), 0, h->stream, p, l, h->cur); break;
+    case 512: hipLaunchKernelGGL((k_select<512>), dim3(p.U), dim3(512), 0, h->stream, p, l, h->cur); break;
+    default: hipLaunchKernelGGL((k_select<1024>), dim3(p.U), dim3(1024), 0, h->stream, p, l, h->cur); break;
   }
   HIPCHK(hipGetLastError());
   if (ev) HIPCHK(hipEventRecord(ev[2], h->stream));
   h->step = l;
   h->cur ^= 1;
+  h->p_step = p;                           // where this step's intermediate arrays lie (ctcbs_peek)
   int polled = -1;
   if (h->cfg.poll_every > 0 && (l % h->cfg.poll_every) == 0) {
     // wait (normally not at all) for the interval before the last one, then look at the count the
@@ -410,13 +415,79 @@ extern "C" int ctcbs_step(ctcbs_t* h, const float* d_att_logp, ctcbs_step_out_t*
     h->known_finished = polled;
   }
   if (out) {
-    const Params& p = h->p;
     out->step = l; out->n_finished = polled;
     out->d_parent = p.out_parent; out->d_token = p.out_token; out->d_score = p.out_score;
     out->d_live = p.out_live; out->d_finished = p.finished; out->d_tau = p.out_tau;
     out->d_tau_end = p.out_tau_end; out->d_eos_added = p.out_eos_added; out->d_stopped = p.out_stopped;
   }
   return CTCBS_OK;
+}
+
+extern "C" int ctcbs_step(ctcbs_t* h, const float* d_att_logp, ctcbs_step_out_t* out) {
+  if (!h || !d_att_logp) return CTCBS_EINVAL;
+  return step_impl(h, h->p, d_att_logp, out);
+}
+
+// ---- the step for callers that cannot allocate --------------------------------------------------
+// Same kernels, same results; the arrays that carry a step's intermediate values from the score kernel
+// to the select kernel (windows, eos scores, the groups' best-first lists, stop flags, work counts) lie
+// in a fixed array in the library's own image instead of memory the handle allocated.  Every GPU holds
+// its own copy of that array at its own address, so its address is asked for once per device.
+#define CTCBS_STATIC_SCRATCH_BYTES (4u << 20)
+#define CTCBS_MAX_DEVICES 64
+static __device__ __align__(256) unsigned char scratch[CTCBS_STATIC_SCRATCH_BYTES];
+static std::mutex g_scratch_mu;
+static unsigned char* g_scratch_ptr[CTCBS_MAX_DEVICES];     // device address of `scratch` on each device (0: not asked yet)
+
+// bytes of the per-step scratch arrays of a handle, each array on a 256-byte boundary
+static size_t static_scratch_need(const Params& p) {
+  const size_t UW = (size_t)p.U * p.Wb, L = UW * p.Wb;
+  auto r = [](size_t n) { return (n + 255) & ~(size_t)255; };
+  return r(UW * 4) * 4 /* win_s, win_e, grp_n, stopped */ + r(UW * 8) * 3 /* ctc_eos, joint_eos, grp_cells */ +
+         r(L * 8) /* grp_J */ + r(L * 4) * 4 /* grp_ci, grp_tok, grp_inc, grp_att */;
+}
+
+__global__ void k_clear_words(int32_t* a, int32_t* b, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) { a[i] = 0; b[i] = 0; }
+}
+
+extern "C" int ctcbs_step_static(ctcbs_t* h, const float* d_att_logp, ctcbs_step_out_t* out) {
+  if (!h || !d_att_logp) return CTCBS_EINVAL;
+  // candidate sets that go through arrays in global memory (more than 256 candidates per hypothesis, or
+  // every id a candidate) would need those arrays here too: not offered
+  if (h->dense_nit || h->p.K > h->score_block) return CTCBS_EINVAL;
+  if (static_scratch_need(h->p) > CTCBS_STATIC_SCRATCH_BYTES) return CTCBS_EINVAL;
+  int dev = -1;
+  HIPCHK(hipGetDevice(&dev));
+  if (dev != h->device || dev < 0 || dev >= CTCBS_MAX_DEVICES) return CTCBS_ESTATE;   // the handle's device must be current
+  unsigned char* base = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+      void* ptr = nullptr;
+      HIPCHK(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+      g_scratch_ptr[dev] = (unsigned char*)ptr;
+    }
+    base = g_scratch_ptr[dev];
+  }
+  if (!base) return CTCBS_EHIP;
+  if (h->known_finished >= h->p.U || h->step >= h->l_cap) return CTCBS_DONE;
+  Params p = h->p;
+  const size_t UW = (size_t)p.U * p.Wb, L = UW * p.Wb;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { unsigned char* q = base + off; off += (bytes + 255) & ~(size_t)255; return q; };
+  p.win_s = (int32_t*)take(UW * 4); p.win_e = (int32_t*)take(UW * 4);
+  p.grp_n = (int32_t*)take(UW * 4); p.stopped = (int32_t*)take(UW * 4);
+  p.ctc_eos = (double*)take(UW * 8); p.joint_eos = (double*)take(UW * 8); p.grp_cells = (long long*)take(UW * 8);
+  p.grp_J = (double*)take(L * 8);
+  p.grp_ci = (int32_t*)take(L * 4); p.grp_tok = (int32_t*)take(L * 4);
+  p.grp_inc = (float*)take(L * 4); p.grp_att = (float*)take(L * 4);
+  // the array keeps what the last call on this GPU (of any handle) left: list lengths and stop flags start
+  // from zero (a fill kernel, not a memset node: the call may be under graph capture)
+  hipLaunchKernelGGL(k_clear_words, dim3((unsigned)((UW + 255) / 256)), dim3(256), 0, h->stream, p.grp_n, p.stopped, (int)UW);
+  HIPCHK(hipGetLastError());
+  return step_impl(h, p, d_att_logp, out);
 }
 
 extern "C" int ctcbs_reset(ctcbs_t* h, const float* d_ctc_logp, const int32_t* h_lens) {
@@ -516,7 +587,7 @@ extern "C" int ctcbs_profile_read(ctcbs_t* h, double* score_ms, double* select_m
 
 extern "C" int ctcbs_peek(ctcbs_t* h, int32_t what, void* h_dst, size_t bytes, size_t* need) {
   if (!h) return CTCBS_EINVAL;
-  const Params& p = h->p;
+  const Params& p = h->step > 0 ? h->p_step : h->p;
   const size_t UW = (size_t)p.U * p.Wb;
   const void* src = nullptr; size_t sz = 0;
   int32_t k = p.K;
