@@ -139,7 +139,7 @@ class Batch:
                     break
             self.n_steps = step
             self.att_ptr = [self.att[i].data_ptr() for i in range(self.l_cap)]
-            res = m.ctcbs_finalize(h, U, self.l_cap)
+            res = m.ctcbs_finalize(h, U, self.l_cap, want_frames=observer is not None)
             stats = m.ctcbs_stats(h)
         finally:
             m.ctcbs_destroy(h)

@@ -81,7 +81,10 @@ def lib():
             getattr(L, name).argtypes = [vp]
         L.orc_ended_get.argtypes = [vp, i32, vp, vp, vp, vp]
         L.orc_hyp_get.argtypes = [vp, i32] + [vp] * 9
-        for name in ("orc_hyp_labels", "orc_hyp_gn", "orc_hyp_gb", "orc_ended_labels"):
+        L.orc_result_frames.restype = i32
+        L.orc_result_frames.argtypes = [vp, vp, vp, i32, ctypes.POINTER(dbl), ctypes.POINTER(i32)]
+        for name in ("orc_hyp_labels", "orc_hyp_gn", "orc_hyp_gb", "orc_ended_labels", "orc_ended_taus",
+                     "orc_hyp_taus"):
             getattr(L, name).restype = vp
             getattr(L, name).argtypes = [vp, i32]
         L.orc_prefix_and_full.restype = i32
@@ -288,8 +291,9 @@ class OracleUtt:
         att, ctc, joint = [v.value for v in d]
         labels = _view(self.L.orc_hyp_labels(self.h, j), np.int32, ln).copy() if ln else \
             np.empty(0, np.int32)
+        taus = _view(self.L.orc_hyp_taus(self.h, j), np.int32, ln).copy() if ln else np.empty(0, np.int32)
         return dict(live=live, len=ln, tau=tau, tau_end=tau_end, rs=rs, re=re, att=att, ctc=ctc,
-                    joint=joint, labels=labels)
+                    joint=joint, labels=labels, taus=taus)
 
     def hyp_gamma(self, j):
         gn = _view(self.L.orc_hyp_gn(self.h, j), np.float64, self.T + 1).copy()
@@ -306,7 +310,9 @@ class OracleUtt:
             n = a.value - 1
             lab = _view(self.L.orc_ended_labels(self.h, i), np.int32, n).copy() if n > 0 else \
                 np.empty(0, np.int32)
-            out.append(dict(len=a.value, tau=b.value, slot=c.value, score=s.value, labels=lab))
+            taus = _view(self.L.orc_ended_taus(self.h, i), np.int32, n).copy() if n > 0 else \
+                np.empty(0, np.int32)
+            out.append(dict(len=a.value, tau=b.value, slot=c.value, score=s.value, labels=lab, taus=taus))
         return out
 
     def result(self):
@@ -317,3 +323,14 @@ class OracleUtt:
         if n < 0:
             raise RuntimeError("orc_result: capacity")
         return lab[:n].copy(), s.value, bool(fb.value)
+
+    def result_frames(self):
+        """-> (labels, time stamp tau of every label, score, fallback flag)"""
+        cap = self.lmax + 1
+        lab = np.zeros(cap, dtype=np.int32)
+        frm = np.zeros(cap, dtype=np.int32)
+        s, fb = ctypes.c_double(), ctypes.c_int32()
+        n = self.L.orc_result_frames(self.h, _p(lab), _p(frm), cap, ctypes.byref(s), ctypes.byref(fb))
+        if n < 0:
+            raise RuntimeError("orc_result_frames: capacity")
+        return lab[:n].copy(), frm[:n].copy(), s.value, bool(fb.value)

@@ -16,7 +16,9 @@
  *     test, final argmax: Algorithm 2 (Algorithm 1 is its one-utterance form).
  *   - Baseline end detection: Eq. (4), M = 3, D_end = e^-10 (log domain: -10).
  *   - Time indices tau / tau~ of the last label: the two argmax equations of
- *     Sec. 3.2.2; tau-count end detection: Algorithm 3, C = 2.
+ *     Sec. 3.2.2; tau-count end detection: Algorithm 3, C = 2.  A hypothesis keeps the tau
+ *     found when each of its labels was appended (the per-label time stamps of Fig. 2(a));
+ *     the tau recorded with an ended hypothesis g.<eos> is tau(g), that of g's last label.
  *   - Time-restricted prefix score and the window [s, e]: Eq. (5) and the two
  *     equations for s and e after it.
  *   Parts that are not in the paper but in this build's brief (top-K attention
@@ -60,6 +62,7 @@ typedef struct {
   int32_t live;
   int32_t len;             /* number of labels                                              */
   int32_t* labels;         /* [cap]                                                         */
+  int32_t* taus;           /* [cap] taus[i] = tau found when labels[i] was appended         */
   double *gn, *gb;         /* [T+1] forward variables, -inf outside [rs, re]                */
   int32_t rs, re;          /* stored range                                                  */
   int32_t tau, tau_end;
@@ -75,6 +78,7 @@ typedef struct {
   int32_t len, tau, slot, step;
   double score;
   int32_t* labels;         /* without eos                                                   */
+  int32_t* taus;           /* time stamp of each label                                      */
 } orc_ended;
 
 typedef struct orc_utt {
@@ -122,10 +126,11 @@ static double f_term(const orc_hyp* g, int t, int c) {
 static void hyp_alloc(orc_hyp* h, int T, int cap) {
   memset(h, 0, sizeof *h);
   h->labels = (int32_t*)calloc((size_t)cap + 1, sizeof(int32_t));
+  h->taus = (int32_t*)calloc((size_t)cap + 1, sizeof(int32_t));
   h->gn = (double*)malloc(sizeof(double) * (size_t)(T + 1));
   h->gb = (double*)malloc(sizeof(double) * (size_t)(T + 1));
 }
-static void hyp_free(orc_hyp* h) { free(h->labels); free(h->gn); free(h->gb); }
+static void hyp_free(orc_hyp* h) { free(h->labels); free(h->taus); free(h->gn); free(h->gb); }
 
 int orc_lmax(const orc_cfg* c, int T) {
   int l = T;                                    /* Algorithm 2 never runs past |h| steps     */
@@ -185,7 +190,7 @@ void orc_destroy(orc_utt* u) {
   free(u->cand_ctc); free(u->cand_att); free(u->cand_joint); free(u->ctc_eos); free(u->joint_eos);
   free(u->e2_eligible); free(u->e2_fire); free(u->e2_margin); free(u->sorted);
   free(u->child_max_n); free(u->child_max_b); free(u->child_lo);
-  for (int i = 0; i < u->n_ended; ++i) free(u->ended[i].labels);
+  for (int i = 0; i < u->n_ended; ++i) { free(u->ended[i].labels); free(u->ended[i].taus); }
   free(u->ended);
   free(u);
 }
@@ -329,6 +334,8 @@ static void add_ended(orc_utt* u, const orc_hyp* g, int slot, double score, int 
   e->len = l; e->tau = g->tau; e->slot = slot; e->step = l; e->score = score;
   e->labels = (int32_t*)malloc(sizeof(int32_t) * (size_t)(g->len + 1));
   memcpy(e->labels, g->labels, sizeof(int32_t) * (size_t)g->len);
+  e->taus = (int32_t*)malloc(sizeof(int32_t) * (size_t)(g->len + 1));
+  memcpy(e->taus, g->taus, sizeof(int32_t) * (size_t)g->len);
 }
 
 /* Algorithm 3 on a plain list of ended hypotheses (length, tau, score): Eq. (4) first,
@@ -432,6 +439,8 @@ int orc_commit(orc_utt* u, int n_sel, const int32_t* sel_parent, const int32_t* 
       if (h->gn[t] > mn) { mn = h->gn[t]; h->tau = t; }
       if (h->gb[t] > mb) { mb = h->gb[t]; h->tau_end = t; }
     }
+    memcpy(h->taus, g->taus, sizeof(int32_t) * (size_t)g->len);
+    h->taus[g->len] = h->tau;                    /* time stamp of the label just appended */
     u->child_max_n[n] = mn; u->child_max_b[n] = mb; u->child_lo[n] = lo;
   }
   orc_hyp* tmp = u->cur; u->cur = u->nxt; u->nxt = tmp;
@@ -462,7 +471,7 @@ void orc_set_union(orc_utt* u, int32_t tau_min, int32_t e_max) { u->union_tau_mi
 void orc_override(orc_utt* u, const int32_t* tau, const int32_t* tau_end, int finished) {
   for (int j = 0; j < u->cfg.beam; ++j) {
     if (!u->cur[j].live) continue;
-    if (tau && tau[j] >= 0) u->cur[j].tau = tau[j];
+    if (tau && tau[j] >= 0) { u->cur[j].tau = tau[j]; if (u->cur[j].len > 0) u->cur[j].taus[u->cur[j].len - 1] = tau[j]; }
     if (tau_end && tau_end[j] >= 0) u->cur[j].tau_end = tau_end[j];
   }
   if (finished >= 0) u->finished = finished;
@@ -477,7 +486,12 @@ int orc_step_auto(orc_utt* u, const float* att) {
 
 /* Final result: argmax over the ended set, earliest added wins ties (Algorithm 2, last line).
  * If nothing ended, the best live hypothesis is returned and *fallback = 1. */
+int orc_result_frames(const orc_utt* u, int32_t* labels, int32_t* frames, int cap, double* score, int32_t* fallback);
 int orc_result(const orc_utt* u, int32_t* labels, int cap, double* score, int32_t* fallback) {
+  return orc_result_frames(u, labels, NULL, cap, score, fallback);
+}
+/* The same with the time stamp of every label (frames may be NULL). */
+int orc_result_frames(const orc_utt* u, int32_t* labels, int32_t* frames, int cap, double* score, int32_t* fallback) {
   int best = -1;
   for (int i = 0; i < u->n_ended; ++i)
     if (best < 0 || u->ended[i].score > u->ended[best].score) best = i;
@@ -485,6 +499,7 @@ int orc_result(const orc_utt* u, int32_t* labels, int cap, double* score, int32_
     int n = u->ended[best].len - 1;
     if (n > cap) return -1;
     memcpy(labels, u->ended[best].labels, sizeof(int32_t) * (size_t)n);
+    if (frames) memcpy(frames, u->ended[best].taus, sizeof(int32_t) * (size_t)n);
     *score = u->ended[best].score; if (fallback) *fallback = 0;
     return n;
   }
@@ -493,6 +508,7 @@ int orc_result(const orc_utt* u, int32_t* labels, int cap, double* score, int32_
     if (u->cur[j].live) {
       if (u->cur[j].len > cap) return -1;
       memcpy(labels, u->cur[j].labels, sizeof(int32_t) * (size_t)u->cur[j].len);
+      if (frames) memcpy(frames, u->cur[j].taus, sizeof(int32_t) * (size_t)u->cur[j].len);
       *score = u->cur[j].joint;
       return u->cur[j].len;
     }
@@ -530,6 +546,7 @@ void orc_ended_get(const orc_utt* u, int i, int32_t* len, int32_t* tau, int32_t*
   *len = u->ended[i].len; *tau = u->ended[i].tau; *slot = u->ended[i].slot; *score = u->ended[i].score;
 }
 const int32_t* orc_ended_labels(const orc_utt* u, int i) { return u->ended[i].labels; }
+const int32_t* orc_ended_taus(const orc_utt* u, int i) { return u->ended[i].taus; }
 /* hypothesis j of the current beam */
 void orc_hyp_get(const orc_utt* u, int j, int32_t* live, int32_t* len, int32_t* tau, int32_t* tau_end,
                  int32_t* rs, int32_t* re, double* att, double* ctc, double* joint) {
@@ -538,6 +555,7 @@ void orc_hyp_get(const orc_utt* u, int j, int32_t* live, int32_t* len, int32_t* 
   *att = h->att; *ctc = h->ctc; *joint = h->joint;
 }
 const int32_t* orc_hyp_labels(const orc_utt* u, int j) { return u->cur[j].labels; }
+const int32_t* orc_hyp_taus(const orc_utt* u, int j) { return u->cur[j].taus; }
 const double* orc_hyp_gn(const orc_utt* u, int j) { return u->cur[j].gn; }
 const double* orc_hyp_gb(const orc_utt* u, int j) { return u->cur[j].gb; }
 

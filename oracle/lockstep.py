@@ -211,19 +211,25 @@ class Lockstep:
     def all_finished(self):
         return all(o.finished for o in self.utts)
 
-    def check_results(self, tokens, ntok, score, flags=None):
-        """Final hypotheses (batch-indexed arrays) against the oracle's ended-set argmax."""
+    def check_results(self, tokens, ntok, score, flags=None, frames=None):
+        """Final hypotheses (batch-indexed arrays) against the oracle's ended-set argmax.  frames: the
+        other side's time stamp (tau) of every label; the oracle's own are those it held when the labels
+        were appended -- including every tau it adopted from the other side inside the tolerance during
+        the steps -- so they must be equal."""
         for o, u in zip(self.utts, self.ids):
-            lab, sc, fb = o.result()
+            lab, frm, sc, fb = o.result_frames()
             got = tokens[u, :ntok[u]]
             if not np.array_equal(got, lab):
                 # a different member of a tie in the ended set is acceptable within EPS
-                ok = any(np.array_equal(got, e["labels"]) and _close(e["score"], sc, self.eps)
-                         for e in o.ended())
-                if ok:
+                ties = [e for e in o.ended() if np.array_equal(got, e["labels"]) and _close(e["score"], sc, self.eps)]
+                if ties:
                     self.report["adopted_fin"] += 1
+                    if frames is not None and not any(np.array_equal(frames[u, :ntok[u]], e["taus"]) for e in ties):
+                        raise ParityError(f"utt {u}: time stamps {frames[u, :ntok[u]].tolist()} of the tied result")
                     continue
                 raise ParityError(f"utt {u}: final labels {got.tolist()} vs oracle {lab.tolist()}")
+            if frames is not None and not np.array_equal(frames[u, :ntok[u]], frm):
+                raise ParityError(f"utt {u}: time stamps {frames[u, :ntok[u]].tolist()} vs oracle {frm.tolist()}")
             if not _close(float(score[u]), sc if np.isfinite(sc) else LOG0, self.eps):
                 raise ParityError(f"utt {u}: final score {score[u]} vs oracle {sc}")
             if flags is not None and bool(flags[u] & 1) != fb:

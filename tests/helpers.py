@@ -160,9 +160,9 @@ def lockstep_decode(w, ctc, lens, peek=True, check_utts=None, max_steps=None, pr
                 progress(step, out)
             if out["finished"].all():
                 break
-        tok, nt, sc, frm, fl = dec.finalize()
+        tok, nt, sc, frm, fl = dec.finalize(frames=True)
         if max_steps is None:
-            ls.check_results(tok, nt, sc, fl)
+            ls.check_results(tok, nt, sc, fl, frames=frm)
         cells, _groups, steps = dec.m.ctcbs_stats(dec.h)
         res = dict(tokens=tok, ntok=nt, score=sc, flags=fl, cells=cells, steps=steps,
                    oracle_cells=sum(o.cells for o in ls.utts))

@@ -52,7 +52,7 @@ def run_sampled(workload, sample, over=None):
             print(f"step {step}: {ls.report}", flush=True)
 
     tok, nt, sc, frm, fl = b.record(observer)
-    ls.check_results(tok, nt, sc, fl)
+    ls.check_results(tok, nt, sc, fl, frames=frm)
     # the timed path (recorded rows replayed, polling every 8 steps) reproduces the recorded decode
     (tok2, nt2, sc2, _, fl2), _ = b.decode()
     assert np.array_equal(tok, tok2) and np.array_equal(nt, nt2) and np.array_equal(sc, sc2)
@@ -64,11 +64,13 @@ def test_cfg2_full_size_sampled_utterances():
     w = gen.workload("cfg2")
     lens = gen.workload_lengths(w)
     order = np.argsort(lens)
-    sample = sorted({int(order[0]), int(order[-1]), int(order[len(order) // 2]), 5, 40})
+    # a quarter of the batch: the shortest, the longest, the median and every fourth by length in between
+    sample = sorted({int(order[0]), int(order[-1]), int(order[len(order) // 2])} | {int(u) for u in order[2::4]})
+    assert len(sample) >= 16
     rep, b = run_sampled("cfg2", sample)
     print(rep, "decode steps", b.n_steps, "cells", b.cells)
     assert rep["max_score_err"] < 1e-4 and rep["max_ctc_err"] < 1e-4
-    assert rep["utt_steps"] > 400
+    assert rep["utt_steps"] > 1500
 
 
 def test_cfg3_one_batch_of_meeting_segments():
@@ -88,6 +90,36 @@ def test_cfg3_one_batch_of_meeting_segments():
     assert rep["max_score_err"] < 1e-4 and rep["max_ctc_err"] < 1e-4
 
 
+def _cfg3_batch(lens, sample):
+    orig = gen.workload_lengths
+    try:
+        gen.workload_lengths = lambda _w: np.ascontiguousarray(lens, dtype=np.int32)
+        return run_sampled("cfg3", sample)
+    finally:
+        gen.workload_lengths = orig
+
+
+def test_cfg3_short_segment_batch_and_the_last_batch_that_is_not_full():
+    """The other ends of the cfg3 job: the batch of the 128 shortest segments, and the job's last batch,
+    which holds fewer segments than slots (unused slots have length 0 and stay inert)."""
+    import paper_2101_05600_amd as m
+    seg = gen.segments(2101)
+    rep, b = _cfg3_batch(seg[:128], [0, 1, 64, 127])
+    print("shortest", rep)
+    assert rep["max_score_err"] < 1e-4 and rep["max_ctc_err"] < 1e-4
+    order, begin = m.ctcbs_plan_batches(seg, 128)
+    ids = order[begin[-2]:begin[-1]]
+    assert 0 < len(ids) < 128
+    lens = np.zeros(128, np.int32)
+    lens[:len(ids)] = seg[ids]
+    n = len(ids)
+    rep, b = _cfg3_batch(lens, [0, n // 2, n - 1])
+    print("last batch", n, "of 128 slots used", rep)
+    assert rep["max_score_err"] < 1e-4 and rep["max_ctc_err"] < 1e-4
+    tok, nt, sc = b.ref[0], b.ref[1], b.ref[2]
+    assert (nt[n:] == 0).all() and (sc[n:] < -1e29).all()          # unused slots: no tokens, score log0
+
+
 def test_cfg4b_full_size_sampled_utterances():
     """U=256 utterances of 1500 frames, beam 20, top-60, window 80/80: the throughput-bound launch
     shape (5120 score work-groups, one-work-group-per-utterance select), two utterances followed
@@ -96,6 +128,16 @@ def test_cfg4b_full_size_sampled_utterances():
     print(rep, "decode steps", b.n_steps, "cells", b.cells)
     assert rep["max_score_err"] < 1e-4 and rep["max_ctc_err"] < 1e-4
     assert rep["utt_steps"] > 500
+
+
+def test_cfg4a_shape_followed_deep_into_the_utterance():
+    """Eq. (3) as it stands at cfg4a's sizes (T = 1500 frames, all 4998 ids, whole-utterance windows): one
+    utterance at beam 4 followed for 120 steps, every candidate's prefix score compared at 1e-4.  This is
+    the regime in which a candidate's own prefix score lies hundreds of nats below its hypothesis's."""
+    rep, b = run_sampled("cfg4a", [0], over=dict(n_utt=2, beam=4, max_len_ratio=0.0, max_len_abs=120))
+    print(rep, "decode steps", b.n_steps, "cells", b.cells)
+    assert b.n_steps == 120 and rep["utt_steps"] == 120
+    assert rep["max_score_err"] < 1e-4 and rep["max_ctc_err"] < 1e-4
 
 
 def test_cfg4a_full_vocabulary_first_steps():

@@ -101,8 +101,9 @@ def test_finalize_equals_backtrack_of_step_outputs():
 def test_cfg1_shape_all_utterances():
     w = gen.workload("cfg1")
     lens, ctc = make_inputs(w)
-    rep, res = lockstep_decode(w, ctc, lens, peek=True, check_utts=[0, 3, 7, 12], max_steps=None)
+    rep, res = lockstep_decode(w, ctc, lens, peek=True, max_steps=None)      # all 16 utterances
     print(rep)
+    assert rep["utt_steps"] > 1200
     assert rep["max_score_err"] < 1e-4 and rep["max_ctc_err"] < 1e-4
 
 

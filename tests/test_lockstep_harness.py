@@ -67,6 +67,14 @@ def test_faithful_stand_in_passes_and_results_agree():
     tok = np.full((1, 20), -1, np.int32); tok[0, :len(lab)] = lab
     ls.check_results(tok, np.array([len(lab)]), np.array([sc], np.float32), np.array([int(fb)]))
     assert ls.report["adopted_sel"] == 0 and ls.report["exact_sel_steps"] == ls.report["utt_steps"]
+    # the per-label time stamps are part of the result: the stand-in's own pass, a wrong frame is caught
+    lab2, frm, _, _ = o.result_frames()
+    assert len(lab) > 1 and list(lab2) == list(lab)
+    frames = np.full((1, 20), -1, np.int32); frames[0, :len(lab)] = frm
+    ls.check_results(tok, np.array([len(lab)]), np.array([sc], np.float32), np.array([int(fb)]), frames=frames)
+    frames[0, len(lab) // 2] += 1
+    with pytest.raises(ParityError, match="time stamps"):
+        ls.check_results(tok, np.array([len(lab)]), np.array([sc], np.float32), np.array([int(fb)]), frames=frames)
 
 
 def test_wrong_token_is_caught():

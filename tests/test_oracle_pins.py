@@ -627,3 +627,165 @@ def test_union_window_is_min_start_max_end_over_the_batch():
                     # never narrower than the hypothesis's own window
                     assert s[j] <= max(h["tau"] - 4, step, 1) and e[j] >= min(h["tau_end"] + 6, o.T)
             o.commit()
+
+
+# --------------------------------------------------------------------------------------
+# Per-label time stamps (Sec. 3.2.2, Fig. 2(a)): the tau found when each label was appended
+# --------------------------------------------------------------------------------------
+def test_result_carries_the_time_stamp_of_every_label():
+    T, V = 60, 6
+    emits = {5: 1, 17: 2, 18: 2, 30: 3, 44: 1}
+    x = peaky_posteriors(T, V, emits)
+    cfg = make_cfg(vocab=V, beam=2, cand_k=0, ctc_weight=0.5, max_len_abs=10, end_flags=0)
+    o = OracleUtt(x, cfg)
+    follow(o, x, [1, 2, 3, 1], V)
+    lab, frm, sc, fb = o.result_frames()
+    assert list(lab) == [1, 2, 3, 1] and not fb
+    assert frm[0] == 5 and frm[1] in (17, 18) and frm[2] == 30 and frm[3] == 44
+    # the tau kept with an ended hypothesis g.<eos> is that of g's last label, and every ended entry
+    # carries the stamps of its own labels
+    for e in o.ended():
+        assert len(e["taus"]) == len(e["labels"])
+        if len(e["labels"]):
+            assert e["tau"] == e["taus"][-1]
+        assert list(e["taus"]) == sorted(e["taus"])          # time stamps never run backwards
+    # an adopted tau (lock-step tolerance) replaces the stamp of the label it belongs to
+    o2 = OracleUtt(x, cfg)
+    att = np.full((2, V), -6.0, np.float32); att[:, 1] = -0.05
+    o2.score(att); o2.commit()
+    assert o2.hyp(0)["taus"].tolist() == [5]
+    o2.override(np.array([6, -1], np.int32), None, -1)
+    assert o2.hyp(0)["tau"] == 6 and o2.hyp(0)["taus"].tolist() == [6]
+
+
+# --------------------------------------------------------------------------------------
+# [brief] eos-run rule E2 against its definition evaluated another way: with unrestricted windows
+# phi_t(g) is the full-sequence probability of g on the first t frames and the running prefix score
+# of g.c up to t is the prefix probability of g.c on the first t frames -- both from the stand-alone
+# routine that the brute-force enumeration pins
+# --------------------------------------------------------------------------------------
+def e2_by_definition(x, labels, cands, R, t_first=None):
+    T = x.shape[0]
+    t_first = T - R + 1 if t_first is None else t_first
+    margin = np.inf
+    for t in range(t_first, T + 1):
+        _, E = prefix_and_full(x[:t], labels)
+        X = max(prefix_and_full(x[:t], list(labels) + [c])[0] for c in cands)
+        d = -np.inf if E == NEG else (np.inf if X == NEG else E - X)
+        margin = min(margin, d)
+    return margin
+
+
+def test_eos_run_rule_equals_its_definition_and_the_frame_range_matters():
+    fires = quiet = early_differs = late_differs = 0
+    for seed in range(60):
+        rng = np.random.default_rng(1000 + seed)
+        T, V, R = 11, 4, 4
+        x = rand_logp(rng, T, V, peaky=2.5)
+        cfg = make_cfg(vocab=V, beam=2, cand_k=0, ctc_weight=0.5, max_len_abs=5, end_flags=4, eos_run=R)
+        o = OracleUtt(x, cfg)
+        while not o.finished:
+            hyps = [o.hyp(j) for j in range(o.B)]
+            att = np.stack([gen.att_row(seed, 0, o.step + 1, gen.prefix_hash(h["labels"]), V) for h in hyps])
+            o.score(att)
+            el, fire, margin = o.e2()
+            s_win, _ = o.windows()
+            for j, h in enumerate(hyps):
+                if not h["live"]:
+                    continue
+                # unrestricted: eligible iff the window and the stored range start early enough
+                assert bool(el[j]) == (max(s_win[j], h["rs"]) <= T - R + 1)
+                if not el[j]:
+                    continue
+                cands = [c for c in range(V) if c not in (0, V - 1)]
+                want = e2_by_definition(x, h["labels"], cands, R)
+                assert (np.isinf(want) and margin[j] == want) or abs(margin[j] - want) < 1e-9
+                assert bool(fire[j]) == (want > 0.0)
+                fires += int(fire[j]); quiet += int(not fire[j])
+                # one frame more, one frame fewer: would the outcome change?
+                if s_win[j] <= T - R:
+                    early_differs += int((e2_by_definition(x, h["labels"], cands, R, T - R) > 0) != bool(fire[j]))
+                late_differs += int((e2_by_definition(x, h["labels"], cands, R, T - R + 2) > 0) != bool(fire[j]))
+            o.commit()
+    assert fires > 5 and quiet > 5
+    assert early_differs > 0 and late_differs > 0      # so a frame range off by one would have been noticed
+
+
+def test_eos_run_eligibility_boundary_and_strict_comparison():
+    # eligibility: the window must start at T - R + 1 at the latest
+    T, V, R = 30, 4, 10
+    x = peaky_posteriors(T, V, {26: 1})
+    for m1, want in ((5, 1), (4, 0)):                  # s = tau - M1 = 21 = T - R + 1, or 22
+        cfg = make_cfg(vocab=V, beam=1, cand_k=0, win_m1=m1, win_m2=-1, ctc_weight=0.5, max_len_abs=9,
+                       end_flags=4, eos_run=R)
+        o = OracleUtt(x, cfg)
+        att = np.full((1, V), -4.0, np.float32); att[0, 1] = -0.1
+        o.score(att); o.commit()
+        assert o.hyp(0)["tau"] == 26
+        o.score(att)
+        s_win, e_win = o.windows()
+        assert s_win[0] == 26 - m1 and e_win[0] == T
+        assert o.e2()[0][0] == want
+    # strictness: E_t == X_t on the deciding frame is not "exceeds".  T = 2, R = 1, g = (1), and log values
+    # (not normalised: the oracle takes any) chosen so that a single path carries each side and no rounding
+    # occurs: label 1 is impossible at frame 2, hence phi_2(g) = x_1(1) + x_2(blank), and the best
+    # extension is psi(g.2) = phi_1(g) + x_2(2) = x_1(1) + x_2(2); with x_2(blank) = x_2(2) they are equal
+    xs = np.array([[-1.0, -0.5, -2.0, -2.0], [-1.0, -np.inf, -1.0, -2.0]], np.float32)
+    cfg = make_cfg(vocab=4, beam=1, cand_k=0, ctc_weight=0.5, max_len_abs=2, end_flags=4, eos_run=1)
+    o = OracleUtt(xs, cfg)
+    att = np.full((1, 4), -4.0, np.float32); att[0, 1] = -0.1
+    o.score(att); o.commit()
+    o.score(att)
+    el, fire, margin = o.e2()
+    assert el[0] and margin[0] == 0.0 and not fire[0]
+    xs2 = xs.copy(); xs2[1, 2] = np.nextafter(xs2[1, 2], np.float32(-2.0))      # X a hair smaller: exceeds
+    o = OracleUtt(xs2, cfg)
+    o.score(att); o.commit(); o.score(att)
+    el, fire, margin = o.e2()
+    assert el[0] and margin[0] > 0.0 and fire[0]
+
+
+# --------------------------------------------------------------------------------------
+# Algorithm 2: "p > best_score" is strict; equal joint scores are ordered by (parent slot, token);
+# the final argmax over the ended set keeps the entry added first among equals
+# --------------------------------------------------------------------------------------
+def test_equal_scores_strictness_and_tie_breaks():
+    V, T = 6, 8
+    x = rand_logp(np.random.default_rng(3), T, V)
+    # lambda = 0: joint scores are sums of attention values, so equal inputs give exactly equal scores
+    cfg = make_cfg(vocab=V, beam=3, cand_k=0, ctc_weight=0.0, max_len_abs=4, end_flags=0)
+    o = OracleUtt(x, cfg)
+    a1 = np.full((3, V), -5.0, np.float32)
+    a1[0, 2] = a1[0, 4] = -1.0                        # two labels with the same score
+    a1[0, 3] = -2.0
+    o.score(a1); o.rank()
+    S = o.sorted_cands()
+    assert [(int(c["parent"]), int(c["token"])) for c in S[:3]] == [(0, 2), (0, 4), (0, 3)]   # equal: token ascending
+    o.commit()
+    assert [list(o.hyp(j)["labels"]) for j in range(3)] == [[2], [4], [3]]
+    # step 2: the two equal hypotheses get identical rows -> equal candidates from different parents
+    a2 = np.full((3, V), -5.0, np.float32)
+    a2[0, 1] = a2[1, 1] = -0.5
+    a2[0, 3] = a2[1, 3] = -0.75
+    a2[:, V - 1] = -0.5                               # eos exactly as good as the best extension
+    o.score(a2); o.rank()
+    S = o.sorted_cands()
+    assert [(int(c["parent"]), int(c["token"])) for c in S[:4]] == [(0, 1), (1, 1), (0, 3), (1, 3)]   # equal: parent ascending
+    je, best = o.joint_eos(), o.best
+    assert je[0] == best and je[1] == best            # equal is not greater: nothing enters the ended set
+    o.commit()
+    assert o.ended() == []
+    # step 3: eos a hair better than every extension for the two equal hypotheses -> two entries of equal score
+    a3 = np.full((3, V), -5.0, np.float32)
+    a3[0, 2] = a3[1, 2] = -0.5
+    a3[0, V - 1] = a3[1, V - 1] = np.nextafter(np.float32(-0.5), np.float32(0.0))
+    hyp0, hyp1 = list(o.hyp(0)["labels"]), list(o.hyp(1)["labels"])
+    assert hyp0 == [2, 1] and hyp1 == [4, 1]
+    o.score(a3); o.commit()
+    ended = o.ended()
+    assert len(ended) == 2 and ended[0]["score"] == ended[1]["score"]
+    assert list(ended[0]["labels"]) == hyp0 and list(ended[1]["labels"]) == hyp1     # slot order
+    while not o.finished:
+        o.score(np.full((3, V), -9.0, np.float32)); o.commit()
+    lab, sc, fb = o.result()
+    assert list(lab) == hyp0 and sc == ended[0]["score"]      # the first of the equal entries
