@@ -229,7 +229,19 @@ def cpu_baseline(batch, n_sample):
         kw[k] = float(np.float32(kw[k]))          # the values the fp32 fields of the C ABI carry
     cfg = oracle.make_cfg(**kw)
     L = oracle.lib()
-    cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")), n)
+    # every host core this job may use: the GPU machine hands each job a share of its cores and says so through
+    # OMP_NUM_THREADS; without that, all the cores the OS shows
+    host_cpus = os.cpu_count() or 1
+    share = int(os.environ.get("OMP_NUM_THREADS", "0")) or host_cpus
+    cores = max(1, min(host_cpus, share, n))
+    cpu_model = "unknown"
+    try:
+        for ln in open("/proc/cpuinfo"):
+            if ln.startswith("model name"):
+                cpu_model = ln.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
 
     def run(utt_ids, threads):
         os.environ["OMP_NUM_THREADS"] = str(threads)
@@ -261,6 +273,9 @@ def cpu_baseline(batch, n_sample):
     L.orc_set_threads(cores)
     cN, tN, nN = run(list(range(n)), cores)
     return {"value": cN / tN, "unit": "cells/s", "cores": cores, "kind": "oracle",
+            "cpu_model": cpu_model, "host_cpus": host_cpus,
+            "cores_note": "all cores of this job's share of the host (OMP_NUM_THREADS as set on the box, "
+                          "else every core the OS shows), capped by the utterances in the sample",
             "sample": f"first {nN} of {batch.U} utterances of the same batch, whole decodes, "
                       f"free-running with host-generated attention rows; oracle calls only "
                       f"({tN:.2f} s on {cores} threads)",
@@ -528,18 +543,32 @@ def main():
     ach = bytes_score / (score_ms * 1e-3) / 1e9
     # measured HBM bytes per launch of the same kernel (rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by a
     # plain copy): taken from the committed counter summary, not measurable from inside this process
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"k_score_{a.workload}_traffic.txt")
+    traffic, prof_us, prof_when = None, None, None
+    tname = f"k_score_{a.workload}_traffic.txt"
+    tpath = os.path.join(ROOT, "profiles", tname)
     if os.path.exists(tpath) and a.utts == 0:           # the counters were read at the workload's own size
         for ln in open(tpath):
             if ln.startswith("traffic_bytes_per_launch:"):
                 traffic = float(ln.split(":")[1])
+            elif ln.startswith("rocprof_avg_launch_us:"):
+                prof_us = float(ln.split(":")[1])
+            elif ln.startswith("measured:"):
+                prof_when = ln.split(":", 1)[1].strip()
     if restricted:
         roof = {"bound": "hbm", "kernel": "k_score", "achieved": ach, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": traffic,
                 "avg_launch_us": score_ms * 1e3 / max(n_prof, 1),
+                "avg_launch_us_how": "HIP events on the library's stream around every launch of one extra decode "
+                                     "(spans the dispatch gap before the kernel: reads about 2 us more than the "
+                                     "kernel's own duration)",
                 "algorithmic_bytes_per_launch": bytes_score / max(n_prof, 1),
-                "select_kernel_avg_us": select_ms * 1e3 / max(n_prof, 1)}
+                "select_kernel_avg_us": select_ms * 1e3 / max(n_prof, 1),
+                # from the committed rocprofv3 summary (a profiler cannot run inside this process): the
+                # kernel's own average duration, the fraction of the roof it gives, and what the HBM counters read
+                "rocprof": {"avg_launch_us": prof_us,
+                            "frac": (bytes_score / max(n_prof, 1) / (prof_us * 1e-6) / 1e9 / HBM_PEAK_GBS) if prof_us else None,
+                            "traffic_bytes_per_launch": traffic, "source": "profiles/" + tname,
+                            "measured": prof_when}}
     else:
         # every id a candidate: the beam slots of an utterance share each posterior column, bytes fall
         # to 4/Wb per term and the bound is the plain ALUs.  Per term one fused multiply-add, one
@@ -548,9 +577,17 @@ def main():
         # the most this instruction mix can reach (the chip's 157.3 TFLOP/s needs an FMA in every slot)
         tf = 4.0 * b.cells / (score_ms * 1e-3) / 1e12
         peak = 256 * 4 * 16 * 2.4e9 / 6.0 * 4.0 / 1e12
+        terms_per_s = b.cells / (score_ms * 1e-3)
         roof = {"bound": "alu", "kernel": "k_score_dense", "achieved": tf, "peak": peak, "unit": "TFLOP/s",
                 "frac": tf / peak, "traffic": None, "avg_launch_us": score_ms * 1e3 / max(n_prof, 1),
-                "flop_per_term": 4, "select_kernel_avg_us": select_ms * 1e3 / max(n_prof, 1)}
+                "flop_per_term": 4, "select_kernel_avg_us": select_ms * 1e3 / max(n_prof, 1),
+                "peak_how": "instruction-mix ceiling derived from the unit counts, not a published chip peak: "
+                            "256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz / 6 issue slots per term x 4 flop",
+                # the same rate against the chip's own figures: one exp2 per term against the transcendental
+                # rate (quarter rate: 256 x 4 x 16 x 2.4e9 / 4 per second), and 4 flop per term against the
+                # published fp32 vector peak
+                "frac_of_transcendental_rate": terms_per_s / (256 * 4 * 16 * 2.4e9 / 4.0),
+                "frac_of_fp32_vector_peak": tf / 157.3}
     line = {
         "metric": "CTC prefix-score cells/sec (utt·beam·cand·frame) + utterances/sec at B=64",
         "value": b.cells / (dt / a.steps), "unit": "cells/s",
@@ -567,6 +604,35 @@ def main():
                    "host_threads": a.threads if a.inflight > 1 else 1},
         "roofline": roof,
     }
+    if a.inflight == 1 and not a.no_offline and a.utts == 0 and restricted and w["n_utt"] <= 64:
+        # the same work when eight such batches are decoded as ONE batch of 8 x U utterances on one handle (one
+        # launch per step over all their groups): the lone batch above stays the headline, this says what
+        # the score kernel does when the launch is large enough to be bound by memory rather than by latency
+        wm = dict(w, n_utt=8 * w["n_utt"])
+        bm = Batch(wm, a.poll_every)
+        bm.record()
+        for _ in range(2):
+            bm.decode()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(5):
+            bm.decode()
+        torch.cuda.synchronize()
+        dtm = (time.perf_counter() - t0) / 5
+        _, pm = bm.decode(profile=True)
+        bytes_m = 4.0 * bm.cells + 8.0 * bm.cells / K + 4.0 * w["vocab"] * bm.groups
+        ach_m = bytes_m / (pm[0] * 1e-3) / 1e9
+        line["multi_batch"] = {"utterances": bm.U, "how": "one handle, one batch of 8 x %d utterances of the same recipe" % w["n_utt"],
+                               "ms_per_decode": dtm * 1e3, "utterances_per_sec": bm.U / dtm, "value": bm.cells / dtm,
+                               "unit": "cells/s", "decode_steps": bm.n_steps,
+                               "roofline": {"bound": "hbm", "kernel": "k_score", "achieved": ach_m, "peak": HBM_PEAK_GBS,
+                                            "unit": "GB/s", "frac": ach_m / HBM_PEAK_GBS,
+                                            "avg_launch_us": pm[0] * 1e3 / max(pm[2], 1),
+                                            "algorithmic_bytes_per_launch": bytes_m / max(pm[2], 1),
+                                            "select_kernel_avg_us": pm[1] * 1e3 / max(pm[2], 1)}}
+        bm.close()
+        del bm
+        torch.cuda.empty_cache()
     if a.inflight == 1 and not a.no_offline:
         # context, not the headline: a queue of copies of the same batch, 8 in flight (own handle and
         # stream each), driven by the library's executor on 4 host threads -- what an offline run with a queue of

@@ -1,5 +1,6 @@
 """Builds the library's HIP sources for the host CPU (g++), for tests only: the sources are copied
-with three textual changes (dynamic LDS declarations, the one inline-assembly barrier, `__shared__`)
+with four textual changes (dynamic LDS declarations, the one inline-assembly barrier, `__shared__`, the
+place of a file-scope array's alignment)
 and compiled against the stand-in header in this folder."""
 import os
 import re
@@ -44,6 +45,8 @@ def _patch(text):
                   r"unsigned char* const \1 = emu::dyn_smem();", text)
     text, n = re.subn(r'asm volatile\("s_waitcnt lgkmcnt\(0\)\\n\\ts_barrier" ::: "memory"\);',
                       "emu::wg_barrier();", text)
+    # (g++ wants the alignment of a file-scope array before `static`)
+    text = re.sub(r"static __device__ __align__\((\d+)\) ", r"alignas(\1) static ", text)
     text = _rewrite_lds(text)
     text = text.replace('#include "../../include/ctcbs.h"', f'#include "{ROOT}/include/ctcbs.h"')
     return text

@@ -39,6 +39,10 @@ CASES = {
     # more than 64 candidates per hypothesis: the group's list is ranked by the whole work-group
     "pivot_k80": (dict(n_utt=1, vocab=1024, beam=2, cand_k=80, win_m1=-1, win_m2=-1, end_flags=3,
                        max_len_ratio=0.3), [12]),
+    # a vocabulary beyond 65535 whose attention rows are constant: the radix selection meets more equal keys
+    # than 16 bits count, and the K smallest ids must come out
+    "radix_wide_ties": (dict(n_utt=1, vocab=66000, beam=1, cand_k=3, win_m1=-1, win_m2=-1, end_flags=3,
+                             max_len_abs=3, max_len_ratio=0.0), [5]),
     # logits in, odd vocabulary (radix selection), one candidate per hypothesis
     "logits_odd_vocab": (dict(n_utt=1, vocab=33, beam=2, cand_k=1, win_m1=3, win_m2=8, end_flags=2, att_is_logits=1,
                               max_len_ratio=0.4), [13]),
@@ -87,20 +91,54 @@ def executor_case():
     print("emu ok executor", flush=True)
 
 
-def main():
-    names = sys.argv[2:] or list(CASES)
-    if "executor" in names:
-        names.remove("executor")
-        executor_case()
-    for name in names:
-        over, lens = CASES[name]
+def static_step_case():
+    """ctcbs_step_static (per-step scratch in the library's fixed array) decodes like ctcbs_step."""
+    plain = m.ctcbs_step
+    m.ctcbs_step = m.ctcbs_step_static
+    try:
+        over, lens = CASES["windowed"]
         w = gen.workload("cfg1")
         w.update(over)
         w["eos_id"] = w["vocab"] - 1
         lens = np.asarray(lens, np.int32)
         ctc = gen.workload_ctc(w, np.maximum(lens, 1))
+        rep, res = lockstep_decode(w, ctc, lens, check_utts=[u for u in range(len(lens)) if lens[u] > 0],
+                                   decoder_cls=EmuDecoder)
+        assert rep["max_score_err"] < 1e-4 and res["cells"] == int(res["oracle_cells"]), rep
+    finally:
+        m.ctcbs_step = plain
+    print("emu ok static_step", flush=True)
+
+
+def main():
+    names = sys.argv[2:] or list(CASES)
+    if "static_step" in names:
+        names.remove("static_step")
+        static_step_case()
+    if "executor" in names:
+        names.remove("executor")
+        executor_case()
+    for name in names:
+        max_steps = None
+        if name.startswith("random:"):      # random:<seed of the list>:<case>[:<steps>], tests/random_cases.py
+            import random_cases
+            parts = name.split(":")
+            seed0, case = parts[1], parts[2]
+            max_steps = int(parts[3]) if len(parts) > 3 else None
+            mode, w, lens = random_cases.case_params(int(case), int(seed0))
+            print(random_cases.describe(int(seed0), int(case), mode, w, lens), flush=True)
+        else:
+            over, lens = CASES[name]
+            w = gen.workload("cfg1")
+            w.update(over)
+            w["eos_id"] = w["vocab"] - 1
+        lens = np.asarray(lens, np.int32)
+        ctc = gen.workload_ctc(w, np.maximum(lens, 1))
         used = [u for u in range(len(lens)) if lens[u] > 0]
         kw = {}
+        if name == "radix_wide_ties":
+            flat = lambda a: np.where(np.isnan(a), a, np.float32(-11.0)).astype(np.float32)
+            kw = dict(att_fn=flat, gpu_att_fn=flat)
         if w.get("att_is_logits"):
             # the library takes unnormalised scores; the oracle takes their log_softmax
             def to_logits(a):
@@ -111,10 +149,11 @@ def main():
                 mx = np.nanmax(z, axis=-1, keepdims=True)
                 return (z - (mx + np.log(np.nansum(np.exp(z - mx), axis=-1, keepdims=True)))).astype(np.float32)
             kw = dict(att_fn=normalised, gpu_att_fn=to_logits)
-        rep, res = lockstep_decode(w, ctc, lens, check_utts=used, decoder_cls=EmuDecoder, **kw)
+        rep, res = lockstep_decode(w, ctc, lens, check_utts=used, decoder_cls=EmuDecoder, max_steps=max_steps, **kw)
         tol = 2e-4 if w.get("att_is_logits") else 1e-4
         assert rep["max_score_err"] < tol and rep["max_ctc_err"] < tol, (name, rep)
-        assert res["cells"] == int(res["oracle_cells"]), (name, res["cells"], res["oracle_cells"])
+        if max_steps is None:
+            assert res["cells"] == int(res["oracle_cells"]), (name, res["cells"], res["oracle_cells"])
         print(f"emu ok {name} steps={rep['utt_steps']} score_err={rep['max_score_err']:.2e}", flush=True)
 
 

@@ -21,7 +21,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 sys.path.insert(0, os.path.join(HERE, "cpu_emu"))
 
+sys.path.insert(0, HERE)
+
 import build_emu  # noqa: E402
+from random_cases import CPU_SUBSET  # noqa: E402
 
 
 def _runtime(name):
@@ -75,7 +78,10 @@ def runs(tmp_path_factory):
     plan = {
         "asan": (asan, ASAN_ENV, dict(sanitize=True),
                  ["windowed", "batch_window", "all_candidates", "all_candidates_few_ids", "logits_odd_vocab",
-                  "pivot", "pivot_k80"]),
+                  "pivot", "pivot_k80", "static_step", "radix_wide_ties"]),
+        # the first steps of a fixed subset of the random configurations that tests/test_gpu_random_configs.py
+        # decodes on the GPU (same table, tests/random_cases.py), device memory starting out as garbage
+        "asan_random": (asan, ASAN_ENV, dict(sanitize=True), [f"random:{a}:{b}:{c}" for a, b, c in CPU_SUBSET]),
         # executor: the job queue with two host threads on two handles
         "tsan": (tsan, TSAN_ENV, dict(sanitize="thread"), ["windowed", "batch_window", "executor"]),
         "tsan_planted": (tsan, TSAN_ENV, dict(sanitize="thread", plant=PLANT), ["windowed"]),
@@ -89,7 +95,7 @@ def runs(tmp_path_factory):
             return "a Python child does not start with this sanitizer runtime preloaded here"
         so = build_emu.build(os.path.join(root, name), **build_kw)
         return _run(so, runtime, env, cases)
-    with ThreadPoolExecutor(max_workers=3) as ex:
+    with ThreadPoolExecutor(max_workers=4) as ex:
         futs = {k: ex.submit(one, k) for k in plan}
         return {k: f.result() for k, f in futs.items()}
 
@@ -105,7 +111,16 @@ def test_kernels_under_address_and_ub_sanitizers(runs):
     r, out = _result(runs, "asan")
     assert r.returncode == 0, out[-4000:]
     assert "ERROR: AddressSanitizer" not in out and "runtime error:" not in out, out[-4000:]
-    assert out.count("emu ok") == 7, out[-2000:]
+    assert out.count("emu ok") == 9, out[-2000:]
+
+
+def test_random_configurations_first_steps_under_address_sanitizer(runs):
+    """The CPU side of the randomised GPU test: the same seeded cases (a fixed subset, first steps), on the
+    kernel sources built for the CPU, under AddressSanitizer + UBSan, device memory poisoned."""
+    r, out = _result(runs, "asan_random")
+    assert r.returncode == 0, out[-4000:]
+    assert "ERROR: AddressSanitizer" not in out and "runtime error:" not in out, out[-4000:]
+    assert out.count("emu ok") == len(CPU_SUBSET), out[-2000:]
 
 
 def test_kernels_under_thread_sanitizer(runs):
