@@ -86,6 +86,25 @@ def test_wrong_token_is_caught():
         run(perturb_at=3, perturb=p)
 
 
+def test_wrong_time_index_is_caught():
+    """A time index that is not a maximiser of the oracle's forward variable (within the tolerance) fails."""
+    cfg = make_cfg(vocab=40, beam=4, cand_k=10, win_m1=10, win_m2=10, ctc_weight=0.3, max_len_abs=14,
+                   end_flags=7, eos_run=5, length_bonus=0.5)
+    x = gen.ctc_utt(4, 0, 70, 40)
+    ls = Lockstep([x], cfg)
+    o = OracleUtt(x, cfg)
+    with pytest.raises(ParityError, match="tau of new slot"):
+        while not o.finished:
+            step = o.step + 1
+            hyps = [o.hyp(j) for j in range(4)]
+            att = np.stack([gen.att_row(1, 0, step, gen.prefix_hash(h["labels"]), 40) if h["live"]
+                            else np.full(40, np.nan, np.float32) for h in hyps])
+            out = stand_in_step(o, att, 4)
+            if step == 5:
+                out["tau"][0, 0] += 7
+            ls.step(att[None], out)
+
+
 def test_score_error_is_caught():
     def p(par, tok, sc, S_all):
         sc[1] += 5e-4
