@@ -162,6 +162,12 @@ __device__ __forceinline__ void lds_barrier() {
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// Between LDS stores of some lanes of a wave and LDS loads of the same addresses by other lanes of that
+// wave.  The hardware needs nothing here (a wave's LDS instructions execute in order, all lanes of an
+// instruction together); the call keeps the compiler from moving LDS accesses across this point and gives
+// a CPU build of the kernels, where lanes are threads, its synchronisation point.
+__device__ __forceinline__ void wave_lds_fence() { __builtin_amdgcn_wave_barrier(); }
+
 // Consistency checks on indices that come from device data (candidate ids, list entries, time
 // indices): a value outside its range is clamped into it, so that no access leaves its array, and
 // the step's error bit is set; ctcbs_finalize then reports CTCBS_ESTATE instead of a result.

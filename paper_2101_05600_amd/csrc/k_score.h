@@ -534,7 +534,11 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p
         }
         inc = (W > 0) ? lse_finish<LPC>(a) : LOG0F;
       }
-      if (q == 0) {
+      if (q == 0 && wave_rank) {
+        // (joint scores and sort keys: one lane per candidate at the end, not one pass per chain here)
+        s_inc[c] = inc;
+        if (e2) s_pre[c] = pre;
+      } else if (q == 0) {
         const float av = (smallk ? s_av[c] : arow[id]) - row_lse;
         const bool valid = inc > LOG0_CLASS;
         const double ctc = valid ? offr + (double)inc : LOG0D;
@@ -638,7 +642,16 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p
       // rank by (joint desc, token asc) on 64-bit keys: one lane of the first wave per candidate
       lds_barrier();                                       // keys and scores complete; the other waves are done
       if (tid >= 64) return;
-      const unsigned long long me = tid < K ? s_key[tid] : 0ull;
+      unsigned long long me = 0ull;
+      if (tid < K) {                                       // joint score (Eq. (1)) and sort key of candidate `tid`
+        const float inc = s_inc[tid], av = s_av[tid] - row_lse;
+        const bool valid = inc > LOG0_CLASS;
+        const double ctc = valid ? offr + (double)inc : LOG0D;
+        const double J = valid ? lam * ctc + (1.0 - lam) * (double)av + jbase : LOG0D;
+        me = joint_key(J, s_cid[tid] & 0xFFFF, valid && J == J);
+        s_J[tid] = J; s_av[tid] = av; s_key[tid] = me;
+      }
+      wave_lds_fence();                                    // keys: written by their lanes, read by all below
       int rank = 0;
       const ulonglong2* k2 = (const ulonglong2*)s_key;
       for (int c = 0; c + 1 < K; c += 2) {

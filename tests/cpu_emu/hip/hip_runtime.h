@@ -263,6 +263,8 @@ inline unsigned long long __ballot(int pred) {
   return m;
 }
 inline int __builtin_amdgcn_readlane(int v, int lane) { return emu::from_lane(v, lane); }
+// (on the GPU a scheduling fence only; here the lanes of a wave are threads and meet)
+inline void __builtin_amdgcn_wave_barrier() { emu::wave_sync(emu::self(), __builtin_return_address(0)); }
 // bits of a 64-bit lane mask (given as its two halves) set below the calling lane, plus `add`
 inline unsigned __builtin_amdgcn_mbcnt_lo(unsigned m, unsigned add) {
   const int l = emu::self().lane;
