@@ -654,7 +654,13 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p
       wave_lds_fence();                                    // keys: written by their lanes, read by all below
       int rank = 0;
       const ulonglong2* k2 = (const ulonglong2*)s_key;
-      for (int c = 0; c + 1 < K; c += 2) {
+      int c = 0;
+      for (; c + 8 <= K; c += 8) {                         // four reads in flight at a time
+        const ulonglong2 o0 = k2[c >> 1], o1 = k2[(c >> 1) + 1], o2 = k2[(c >> 1) + 2], o3 = k2[(c >> 1) + 3];
+        rank += ((int)(o0.x > me) + (int)(o0.y > me)) + ((int)(o1.x > me) + (int)(o1.y > me)) +
+                ((int)(o2.x > me) + (int)(o2.y > me)) + ((int)(o3.x > me) + (int)(o3.y > me));
+      }
+      for (; c + 1 < K; c += 2) {
         const ulonglong2 o = k2[c >> 1];
         rank += (int)(o.x > me) + (int)(o.y > me);
       }
