@@ -605,34 +605,38 @@ def main():
         "roofline": roof,
     }
     if a.inflight == 1 and not a.no_offline and a.utts == 0 and restricted and w["n_utt"] <= 64:
-        # the same work when eight such batches are decoded as ONE batch of 8 x U utterances on one handle (one
-        # launch per step over all their groups): the lone batch above stays the headline, this says what
-        # the score kernel does when the launch is large enough to be bound by memory rather than by latency
-        wm = dict(w, n_utt=8 * w["n_utt"])
-        bm = Batch(wm, a.poll_every)
-        bm.record()
-        for _ in range(2):
-            bm.decode()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(5):
-            bm.decode()
-        torch.cuda.synchronize()
-        dtm = (time.perf_counter() - t0) / 5
-        _, pm = bm.decode(profile=True)
-        bytes_m = 4.0 * bm.cells + 8.0 * bm.cells / K + 4.0 * w["vocab"] * bm.groups
-        ach_m = bytes_m / (pm[0] * 1e-3) / 1e9
-        line["multi_batch"] = {"utterances": bm.U, "how": "one handle, one batch of 8 x %d utterances of the same recipe" % w["n_utt"],
-                               "ms_per_decode": dtm * 1e3, "utterances_per_sec": bm.U / dtm, "value": bm.cells / dtm,
-                               "unit": "cells/s", "decode_steps": bm.n_steps,
-                               "roofline": {"bound": "hbm", "kernel": "k_score", "achieved": ach_m, "peak": HBM_PEAK_GBS,
-                                            "unit": "GB/s", "frac": ach_m / HBM_PEAK_GBS,
-                                            "avg_launch_us": pm[0] * 1e3 / max(pm[2], 1),
-                                            "algorithmic_bytes_per_launch": bytes_m / max(pm[2], 1),
-                                            "select_kernel_avg_us": pm[1] * 1e3 / max(pm[2], 1)}}
-        bm.close()
-        del bm
-        torch.cuda.empty_cache()
+        # the same work when several such batches are decoded as ONE batch of n x U utterances on one handle (one
+        # launch per step over all their groups): the lone batch above stays the headline, these say what
+        # the score kernel does as the launch grows from latency-bound towards memory-bound
+        def multi(n):
+            wm = dict(w, n_utt=n * w["n_utt"])
+            bm = Batch(wm, a.poll_every)
+            bm.record()
+            for _ in range(2):
+                bm.decode()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(5):
+                bm.decode()
+            torch.cuda.synchronize()
+            dtm = (time.perf_counter() - t0) / 5
+            _, pm = bm.decode(profile=True)
+            bytes_m = 4.0 * bm.cells + 8.0 * bm.cells / K + 4.0 * w["vocab"] * bm.groups
+            ach_m = bytes_m / (pm[0] * 1e-3) / 1e9
+            out = {"utterances": bm.U, "how": "one handle, one batch of %d x %d utterances of the same recipe" % (n, w["n_utt"]),
+                   "ms_per_decode": dtm * 1e3, "utterances_per_sec": bm.U / dtm, "value": bm.cells / dtm,
+                   "unit": "cells/s", "decode_steps": bm.n_steps,
+                   "roofline": {"bound": "hbm", "kernel": "k_score", "achieved": ach_m, "peak": HBM_PEAK_GBS,
+                                "unit": "GB/s", "frac": ach_m / HBM_PEAK_GBS,
+                                "avg_launch_us": pm[0] * 1e3 / max(pm[2], 1),
+                                "algorithmic_bytes_per_launch": bytes_m / max(pm[2], 1),
+                                "select_kernel_avg_us": pm[1] * 1e3 / max(pm[2], 1)}}
+            bm.close()
+            del bm
+            torch.cuda.empty_cache()
+            return out
+        line["multi_batch"] = multi(8)
+        line["multi_batch_32"] = multi(32)
     if a.inflight == 1 and not a.no_offline:
         # context, not the headline: a queue of copies of the same batch, 8 in flight (own handle and
         # stream each), driven by the library's executor on 4 host threads -- what an offline run with a queue of
