@@ -400,6 +400,21 @@ def run_job(a):
                    "decode_steps_total": sum(b.n_steps for b in batches), "cells_per_job": cells}}))
 
 
+def read_profile_summary(path):
+    """(HBM bytes per launch, the kernel's own average duration in us, when and on what it was measured) from a
+    committed counter summary under profiles/, None for what the file does not hold."""
+    traffic, prof_us, prof_when = None, None, None
+    if os.path.exists(path):
+        for ln in open(path):
+            if ln.startswith("traffic_bytes_per_launch:"):
+                traffic = float(ln.split(":")[1].split()[0])
+            elif ln.startswith("rocprof_avg_launch_us:"):
+                prof_us = float(ln.split(":")[1].split()[0])
+            elif ln.startswith("measured:"):
+                prof_when = ln.split(":", 1)[1].strip()
+    return traffic, prof_us, prof_when
+
+
 def floor(a):
     """Latency floor of one score launch at the headline shape (U=64, beam 10, V=5000, top-40, window
     50/50): the chain of dependent loads alone.  Synthetic buffers of the real sizes; every repetition
@@ -543,17 +558,9 @@ def main():
     ach = bytes_score / (score_ms * 1e-3) / 1e9
     # measured HBM bytes per launch of the same kernel (rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by a
     # plain copy): taken from the committed counter summary, not measurable from inside this process
-    traffic, prof_us, prof_when = None, None, None
     tname = f"k_score_{a.workload}_traffic.txt"
-    tpath = os.path.join(ROOT, "profiles", tname)
-    if os.path.exists(tpath) and a.utts == 0:           # the counters were read at the workload's own size
-        for ln in open(tpath):
-            if ln.startswith("traffic_bytes_per_launch:"):
-                traffic = float(ln.split(":")[1])
-            elif ln.startswith("rocprof_avg_launch_us:"):
-                prof_us = float(ln.split(":")[1])
-            elif ln.startswith("measured:"):
-                prof_when = ln.split(":", 1)[1].strip()
+    traffic, prof_us, prof_when = (read_profile_summary(os.path.join(ROOT, "profiles", tname))
+                                   if a.utts == 0 else (None, None, None))   # read at the workload's own size
     if restricted:
         roof = {"bound": "hbm", "kernel": "k_score", "achieved": ach, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": traffic,

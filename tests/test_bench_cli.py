@@ -21,3 +21,14 @@ def test_product_path_does_not_import_the_oracle():
     assert r.returncode == 0 and r.stdout.strip() == "False"
     src = open(os.path.join(ROOT, "paper_2101_05600_amd", "__init__.py")).read()
     assert "import oracle" not in src and "from oracle" not in src
+
+
+def test_committed_counter_summaries_are_readable_by_the_bench_line():
+    """The roofline object's profiler-side figures come from the committed summaries under profiles/:
+    each must parse and carry traffic, the kernel's own duration and when it was measured."""
+    sys.path.insert(0, ROOT)
+    import bench
+    for wl in ("cfg2", "cfg4b"):
+        traffic, us, when = bench.read_profile_summary(os.path.join(ROOT, "profiles", f"k_score_{wl}_traffic.txt"))
+        assert traffic and traffic > 1e6 and us and 1.0 < us < 1000.0 and when and "MI355X" in when
+    assert bench.read_profile_summary(os.path.join(ROOT, "profiles", "no_such_file.txt")) == (None, None, None)
