@@ -282,6 +282,7 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p
   __shared__ int s_nvalid;
   __shared__ __align__(8) float s_red[4 * (BLOCK / 64)];   // BLOCK/64 floats, then BLOCK/64 doubles
   __shared__ double s_eos[2];                              // eos scores, computed early, written at the end
+  __shared__ float s_e2f[2 * MAX_EOS_RUN];                 // eos-run rule: f terms of the last R frames (both kinds)
 
   const int tid = threadIdx.x;
   const int u = blockIdx.y;
@@ -419,15 +420,28 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p
       }
     }
   };
-  for (int i = tid; i < Wp; i += BLOCK) {
-    float f, fb;
-    f_terms(t0 + i, f, fb);
-    s_F[i] = f; s_Fb[i] = fb;
-  }
   const int R = p.eos_run;
   const bool e2 = (p.end_flags & 4) && R > 0 && T >= R && W > 0 && e == T && re == T &&
                   max(s, rs) <= T - R + 1;
+  const bool wave_rank = smallk && K <= 64 && V <= 65536;  // the group's list is ranked by one wave on 64-bit keys
+  // eos-run rule with few candidates: the f terms of the last R frames are kept apart (and left out of the
+  // window's arrays), so that the sums below stop at frame T - R; the first wave completes them at the end
+  const bool e2w = e2 && wave_rank;
+  const bool e2g = e2 && !wave_rank;                       // the rule by the whole work-group (many candidates)
+  for (int i = tid; i < Wp; i += BLOCK) {
+    float f, fb;
+    f_terms(t0 + i, f, fb);
+    const int k = t0 + i - (T - R + 1);
+    if (e2w && k >= 0 && k < R) { s_e2f[k] = f; s_e2f[MAX_EOS_RUN + k] = fb; f = LOG0F; fb = LOG0F; }
+    s_F[i] = f; s_Fb[i] = fb;
+  }
   const double lam = p.lambda, jbase = (1.0 - lam) * acum + p.beta * (double)l;
+  // eos-run rule: E_t = phi_t(g) of frame t = T-R+1+tid, fetched now so that the test at the end does not wait for it
+  float e2_Et = LOG0F;
+  if (e2 && tid < R) {
+    const int t = T - R + 1 + tid;
+    e2_Et = canon0(lae(gn[t], gb[t]) + (float)(Bu[t] - Bref));
+  }
   if (tid == 0) {
     // eos: phi_T(g) = off' + B_T + stored
     const float ce = (rs <= T && re >= T) ? canon0(lae(eos_n, eos_b)) : LOG0F;
@@ -478,7 +492,6 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p
   constexpr int NSG = BLOCK / LPC;
   const int sg = tid / LPC, q = tid % LPC;
   const float* xu = p.xT + (size_t)u * V * p.Tp;
-  const bool wave_rank = smallk && K <= 64 && V <= 65536;  // the group's list is ranked by one wave on 64-bit keys
   float* g_inc = p.cand_inc + (size_t)grp * K;
   float* g_catt = p.cand_att + (size_t)grp * K;
   double* g_ctc = p.cand_ctc + (size_t)grp * K;
@@ -505,7 +518,9 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p
       float inc = LOG0F, pre = LOG0F;
       {
         Lse a; a.m = LOG0F; a.s = 0.0f;
-        if (!e2) {
+        // (with more column loads in flight the compiler has no register to spare for the extra case: there the
+        // one-wave form takes the two-part path too; its second part is then empty)
+        if ((CB * IT <= 6) ? !e2g : !e2) {
 #pragma unroll
           for (int it = 0; it < IT; ++it) {
             const int i = q + it * LPC;
@@ -513,31 +528,37 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p
           }
           for (int i = q + IT * LPC; i < n4; i += LPC) lse_add4(a, col[i], f4[i]);
         } else {
-          Lse ap; ap.m = LOG0F; ap.s = 0.0f;
-          auto upto = [&](const float4 xv, const float4 fv, int tb) {
-            const int tc = T - R;
+          // the sum in two parts: frames up to T - R (needed on its own below) and the last R frames,
+          // which only the few lanes at the window's end hold
+          Lse aq; aq.m = LOG0F; aq.s = 0.0f;
+          const int tc = T - R;
+          auto split = [&](const float4 xv, const float4 fv, int tb) {
             float4 fc;
             fc.x = tb <= tc ? fv.x : LOG0F; fc.y = tb + 1 <= tc ? fv.y : LOG0F;
             fc.z = tb + 2 <= tc ? fv.z : LOG0F; fc.w = tb + 3 <= tc ? fv.w : LOG0F;
-            lse_add4(ap, xv, fc);
+            lse_add4(a, xv, fc);
+            if (tb + 3 > tc) {
+              fc.x = tb > tc ? fv.x : LOG0F; fc.y = tb + 1 > tc ? fv.y : LOG0F;
+              fc.z = tb + 2 > tc ? fv.z : LOG0F; fc.w = tb + 3 > tc ? fv.w : LOG0F;
+              lse_add4(aq, xv, fc);
+            }
           };
 #pragma unroll
           for (int it = 0; it < IT; ++it) {
             const int i = q + it * LPC;
-            if (i < n4) { lse_add4(a, x[b][it], f4[i]); upto(x[b][it], f4[i], t0 + 4 * i); }
+            if (i < n4) split(x[b][it], f4[i], t0 + 4 * i);
           }
-          for (int i = q + IT * LPC; i < n4; i += LPC) {
-            const float4 xv = col[i];
-            lse_add4(a, xv, f4[i]); upto(xv, f4[i], t0 + 4 * i);
-          }
-          pre = lse_finish<LPC>(ap);
+          for (int i = q + IT * LPC; i < n4; i += LPC) split(col[i], f4[i], t0 + 4 * i);
+          pre = lse_finish<LPC>(a);
+          const float mn = fmaxf(a.m, aq.m);                // whole window: both parts
+          a.s = a.s * __expf(a.m - mn) + aq.s * __expf(aq.m - mn);
+          a.m = mn;
         }
         inc = (W > 0) ? lse_finish<LPC>(a) : LOG0F;
       }
       if (q == 0 && wave_rank) {
         // (joint scores and sort keys: one lane per candidate at the end, not one pass per chain here)
-        s_inc[c] = inc;
-        if (e2) s_pre[c] = pre;
+        s_inc[c] = inc;                                    // (eos-run rule armed: the sum up to frame T - R so far)
       } else if (q == 0) {
         const float av = (smallk ? s_av[c] : arow[id]) - row_lse;
         const bool valid = inc > LOG0_CLASS;
@@ -560,8 +581,9 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p
 
   TRACE_MARK(4);
   // ---------------- 4. eos-run rule, group list, outputs -----------------------------------
+  // (few candidates: the first wave runs this test alone, further down, without a barrier)
   int fire = 0;
-  if (e2) {
+  if (e2 && !wave_rank) {
     // Frame T is one of the R frames and there X_T is simply the best full prefix score of the
     // extensions, which is already known: most eligible hypotheses fail this test and skip the rest.
     if (smallk) lds_barrier(); else __syncthreads();       // s_inc / g_inc of all candidates written
@@ -579,10 +601,10 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p
     const bool maybe = (ET > LOG0_CLASS) && (XT < LOG0_CLASS || ET > XT);
     lds_barrier();                                         // s_e2w is reused below
     if (maybe) {
-    // the last R frames, eight at a time (few registers: this path is rare): every lane carries the
+    // the last R frames, sixteen at a time: every lane carries the
     // running prefix score of its candidates from chunk to chunk through the pre array (each entry
     // is only ever touched by one lane from here on) and keeps, per frame, the best score it has seen
-    constexpr int E2C = 8;
+    constexpr int E2C = 16;
     for (int k0 = 0; k0 < R; k0 += E2C) {
       float xmax[E2C];
 #pragma unroll
@@ -616,8 +638,7 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p
     if (tid == 0) s_nvalid = 1;                            // reused as the "all frames passed" flag
     lds_barrier();
     if (tid < R) {
-      const int t = T - R + 1 + tid;
-      const float Et = canon0(lae(gn[t], gb[t]) + (float)(Bu[t] - Bref));
+      const float Et = e2_Et;
       float X = s_e2w[tid];
 #pragma unroll
       for (int w2 = 1; w2 < BLOCK / 64; ++w2) X = fmaxf(X, s_e2w[w2 * MAX_EOS_RUN + tid]);
@@ -630,18 +651,66 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p
     }                                                      // maybe
     lds_barrier();                                         // s_nvalid is reset below
   }
-  if (tid == 0) {
+  auto group_outputs = [&]() {
     p.stopped[grp] = fire;
     p.ctc_eos[grp] = s_eos[0]; p.joint_eos[grp] = s_eos[1];
     p.win_s[grp] = s; p.win_e[grp] = e;
     p.grp_cells[grp] = (long long)K * (long long)W;
-  }
+  };
+  if (!wave_rank && tid == 0) group_outputs();
 
   if (smallk) {
     if (wave_rank) {
-      // rank by (joint desc, token asc) on 64-bit keys: one lane of the first wave per candidate
-      lds_barrier();                                       // keys and scores complete; the other waves are done
+      // one lane of the first wave per candidate from here on
+      constexpr int E2W = 16;                              // eos-run rule: frames per round of loads
+      constexpr bool E2_EARLY = (CB * IT <= 6);            // (the forms with more column loads in flight have no registers to spare)
+      float xv0[E2_EARLY ? E2W : 1];
+      if (E2_EARLY && e2 && tid < 64) {                    // the candidate's posteriors of the last R frames: on
+        const float* colf = xu + (size_t)s_cid[tid < K ? tid : 0] * p.Tp;   // their way while the other waves finish
+#pragma unroll
+        for (int k = 0; k < E2W; ++k) xv0[k] = colf[min(T - R + 1 + k, T)];
+      }
+      lds_barrier();                                       // prefix scores complete; the other waves are done
       if (tid >= 64) return;
+      if (e2) {
+        // eos-run rule by one wave.  The sums so far stop at frame T - R; walking through the last R frames
+        // completes them and gives, on the way, X_t = best running prefix score of the extensions at frame
+        // t, to be held against E_t (in lane t - (T-R+1) since the start of the kernel).
+        const bool has = tid < K;
+        auto wave_max = [](float v) {
+          v = row16_max(v);
+          return fmaxf(fmaxf(lane_f(v, 0), lane_f(v, 16)), fmaxf(lane_f(v, 32), lane_f(v, 48)));
+        };
+        const int e2id = s_cid[has ? tid : 0];
+        const float* colf = xu + (size_t)e2id * p.Tp;
+        const float* ff = s_e2f + ((e2id == last) ? MAX_EOS_RUN : 0);
+        float acc = has ? s_inc[tid] : LOG0F;
+        fire = 1;
+        for (int k0 = 0; k0 < R; k0 += E2W) {
+          float xv[E2W];
+          if (E2_EARLY && k0 == 0) {
+#pragma unroll
+            for (int k = 0; k < E2W; ++k) xv[k] = xv0[E2_EARLY ? k : 0];
+          } else {
+#pragma unroll
+            for (int k = 0; k < E2W; ++k) xv[k] = colf[min(T - R + 1 + k0 + k, T)];   // all loads in flight
+          }
+#pragma unroll
+          for (int k = 0; k < E2W; ++k) {
+            if (k0 + k < R) {                              // (uniform)
+              acc = lae(acc, ff[k0 + k] + xv[k]);
+              const float X = wave_max(has ? canon0(acc) : -3.0e38f);
+              const float Et = k0 == 0 ? lane_f(e2_Et, k) : lane_f(e2_Et, k + E2W);
+              // E_t > X_t with log0 on the left never true, log0 on the right always true
+              if (!((Et > LOG0_CLASS) && (X < LOG0_CLASS || Et > X))) fire = 0;
+            }
+          }
+        }
+        if (has) s_inc[tid] = canon0(acc);                 // the whole window's sum
+        wave_lds_fence();
+      }
+      if (tid == 0) group_outputs();
+      // rank by (joint desc, token asc) on 64-bit keys
       unsigned long long me = 0ull;
       if (tid < K) {                                       // joint score (Eq. (1)) and sort key of candidate `tid`
         const float inc = s_inc[tid], av = s_av[tid] - row_lse;

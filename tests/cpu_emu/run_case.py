@@ -43,6 +43,10 @@ CASES = {
     # than 16 bits count, and the K smallest ids must come out
     "radix_wide_ties": (dict(n_utt=1, vocab=66000, beam=1, cand_k=3, win_m1=-1, win_m2=-1, end_flags=3,
                              max_len_abs=3, max_len_ratio=0.0), [5]),
+    # window margins beyond 128 frames: the score kernel's form with four float4 per lane in flight, eos-run
+    # rule armed (its one-wave walk through the last frames after a two-part sum whose second part is empty)
+    "wide_window_eos_run": (dict(n_utt=2, vocab=40, beam=2, cand_k=6, win_m1=70, win_m2=70, end_flags=7, eos_run=3,
+                                 max_len_ratio=0.4), [22, 15]),
     # logits in, odd vocabulary (radix selection), one candidate per hypothesis
     "logits_odd_vocab": (dict(n_utt=1, vocab=33, beam=2, cand_k=1, win_m1=3, win_m2=8, end_flags=2, att_is_logits=1,
                               max_len_ratio=0.4), [13]),
