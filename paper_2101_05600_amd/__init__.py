@@ -21,8 +21,11 @@ END_BASELINE, END_TAU_COUNT, END_EOS_RUN = 1, 2, 4
 PEEK_CAND_ID, PEEK_CAND_CTC, PEEK_CAND_JOINT, PEEK_WIN_S, PEEK_WIN_E = 1, 2, 3, 4, 5
 PEEK_CTC_EOS, PEEK_JOINT_EOS, PEEK_N_CAND = 6, 7, 8
 
+# (kernarg preload: the leading plain arguments of a kernel -- up to 16 dwords -- are handed to its waves in
+# registers when they start; the score and the split select kernel keep what their first loads need there)
 HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+             "-mllvm", "-amdgpu-kernarg-preload-count=16"]
 
 EXPORTS = ["ctcbs_create", "ctcbs_step", "ctcbs_step_static", "ctcbs_poll", "ctcbs_finalize", "ctcbs_stats", "ctcbs_peek",
            "ctcbs_destroy", "ctcbs_strerror", "ctcbs_last_hip_error", "ctcbs_profile",

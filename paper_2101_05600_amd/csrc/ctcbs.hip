@@ -335,7 +335,8 @@ static hipError_t launch_score(ctcbs* h, const Params& p, const float* att, int 
   // selection then reads them element by element (slower, equivalent)
   const int flags = (((uintptr_t)att & 15) == 0 && p.V % 4 == 0) ? 1 : 0;
   hipLaunchKernelGGL((k_score<BLOCK, LPC, CB, IT>), dim3(p.Wb, p.U), dim3(BLOCK), h->score_smem_bytes,
-                     h->stream, p, h->sm, att, l, h->cur, flags);
+                     h->stream, (const HypRec*)p.rec[h->cur], (const UttInfo*)p.uinfo, (const uint32_t*)p.finished,
+                     att, (int)p.Wb, (int)p.V, flags, l, p, h->sm, h->cur);
   return hipGetLastError();
 }
 
@@ -392,7 +393,9 @@ static int step_impl(ctcbs_t* h, const Params& p, const float* d_att_logp, ctcbs
   const bool split = !p.win_union && p.U * p.Wb <= 2048;
   const size_t split_lds = (size_t)28 * p.Wb * p.Wb + 64;
   if (split) {
-    hipLaunchKernelGGL((k_select_split<256>), dim3(p.U * p.Wb), dim3(256), split_lds, h->stream, p, l, h->cur);
+    hipLaunchKernelGGL((k_select_split<256>), dim3(p.U * p.Wb), dim3(256), split_lds, h->stream,
+                       (const HypRec*)p.rec[h->cur], p.utt, (const int32_t*)p.grp_n, (const double*)p.grp_J,
+                       (const int32_t*)p.grp_tok, (const float*)p.grp_inc, (const float*)p.grp_att, (int)p.Wb, l, p, h->cur);
   } else switch (h->select_block) {
     case 256: hipLaunchKernelGGL((k_select<256>), dim3(p.U), dim3(256), 0, h->stream, p, l, h->cur); break;
     case 512: hipLaunchKernelGGL((k_select<512>), dim3(p.U), dim3(512), 0, h->stream, p, l, h->cur); break;

@@ -271,9 +271,15 @@ __device__ __forceinline__ unsigned long long joint_key(double J, int tok, bool 
 }
 
 // Grid: (Wb, U).  flags bit 0: the attention rows start on 16-byte boundaries.
+// The arguments in front of the parameter block are what the first loads of a work-group need (the records
+// of the current buffer = p.rec[cur], p.uinfo, p.finished as words, the attention rows, p.Wb, p.V): as plain
+// leading arguments they are handed to the wave in registers when it starts (kernel-argument preload),
+// so that the record's load does not have to wait for a load of the argument block first.
 template <int BLOCK, int LPC, int CB, int IT>
-__global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p, ScoreSmem sm, const float* __restrict__ att,
-                                                 int l, int cur, int flags) {
+__global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(const HypRec* __restrict__ rec_now,
+                                                 const UttInfo* __restrict__ uinfo, const uint32_t* __restrict__ fin_words,
+                                                 const float* __restrict__ att, int Wb, int V, int flags, int l,
+                                                 Params p, ScoreSmem sm, int cur) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ uint32_t s_scan[BLOCK / 64 + 1];
   __shared__ uint32_t s_w[2 * (BLOCK / 64)];
@@ -286,25 +292,24 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(Params p
 
   const int tid = threadIdx.x;
   const int u = blockIdx.y;
-  const int grp = u * p.Wb + blockIdx.x;
+  const int grp = u * Wb + blockIdx.x;
+  // first round of loads, g's record and the utterance's constants: one 64-byte line and one 16-byte entry
+  // through the scalar path (uniform addresses, nothing in this kernel writes them)
+  const HypRec rec = rec_now[grp];
+  const UttInfo ui = uinfo[u];
+  // (the utterance's finished byte is fetched as part of its aligned word: a uniform word load
+  // can take the scalar path, a byte load cannot)
+  const uint32_t fin_word = fin_words[u >> 2];
   TRACE_DECL;
-  const int K = p.K, V = p.V;
+  const int K = p.K;
   const bool smallk = (K <= BLOCK);
 
-  // ---------------- first round of loads: the attention row and g's record -------------------
-  // The row loads need nothing but the kernel's arguments and go first, all in flight together
-  // (clamped, unconditional: whether the slot holds a hypothesis is only known once its record
-  // is back, and a dead slot's row is valid memory whose values are never looked at).  The
-  // record, one 64-byte line, comes through the scalar path (uniform address, nothing in this
-  // kernel writes it), as do the utterance's constants.
+  // ---------------- the attention row -----------------------------------------------------------
+  // As soon as the record says that the slot holds a hypothesis its row is fetched, all loads in
+  // flight together (a dead slot fetches nothing).
   const float* arow = att + (size_t)grp * V;
   const bool in_regs = p.restricted && (V & 3) == 0 && (V >> 2) <= PIVOT_NV4 * BLOCK && (flags & 1);
   float4 arow_r[PIVOT_NV4];
-  const HypRec rec = p.rec[cur][grp];
-  const UttInfo ui = p.uinfo[u];
-  // (the utterance's finished byte is fetched as part of its aligned word: a uniform word load
-  // can take the scalar path, a byte load cannot)
-  const uint32_t fin_word = ((const uint32_t*)p.finished)[u >> 2];
   const int dead = (int)((fin_word >> (8 * (u & 3))) & 0xffu) | (rec.live == 0);
   if (in_regs && !dead) {
     const float4* a4 = (const float4*)arow;

@@ -482,11 +482,17 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
 // is taken from the step number at which the utterance finished (0 or the current step both
 // mean no).
 // Dynamic LDS: 28 * Wb * Wb + 64 bytes (the list entries).
+// The arguments in front of the parameter block are what the first round of loads needs (p.rec[cur], p.utt,
+// p.grp_n and the list arrays, p.Wb): plain leading arguments reach the wave in registers when it starts
+// (kernel-argument preload), so that those loads do not wait for a load of the argument block first.
 template <int BLOCK>
-__global__ __launch_bounds__(BLOCK) void k_select_split(Params p, int l, int cur) {
+__global__ __launch_bounds__(BLOCK) void k_select_split(const HypRec* __restrict__ rec_now, UttState* __restrict__ utt,
+                                                        const int32_t* __restrict__ grp_n, const double* __restrict__ grp_J,
+                                                        const int32_t* __restrict__ grp_tok, const float* __restrict__ grp_inc,
+                                                        const float* __restrict__ grp_att, int Wb, int l, Params p, int cur) {
   static_assert(BLOCK >= 128, "wave 0 and wave 1 have different jobs");
   extern __shared__ __align__(16) unsigned char split_smem[];
-  const int NE = p.Wb * p.Wb;
+  const int NE = Wb * Wb;
   unsigned long long* s_key = (unsigned long long*)split_smem;        // [NE + 8]
   double* s_J = (double*)(s_key + NE + 8);                            // [NE]
   int* s_tok = (int*)(s_J + NE);                                      // [NE]
@@ -499,9 +505,8 @@ __global__ __launch_bounds__(BLOCK) void k_select_split(Params p, int l, int cur
   __shared__ int s_pick[2];                // entry ranked n, entry ranked 0
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int Wb = p.Wb;
   const int u = blockIdx.x / Wb, n = blockIdx.x - u * Wb;
-  UttState* us = p.utt + u;
+  UttState* us = utt + u;
   const int fs = us->finished_step;        // (tested after the first round of loads is on its way)
   const int nxt = cur ^ 1;
   const size_t h0 = (size_t)u * Wb;
@@ -511,8 +516,8 @@ __global__ __launch_bounds__(BLOCK) void k_select_split(Params p, int l, int cur
   // ---- round 1: every independent load ------------------------------------------------------
   if (tid < Wb) {
     const size_t h = h0 + tid;
-    const HypRec r = p.rec[cur][h];
-    o_live[tid] = r.live; o_n[tid] = p.grp_n[h]; o_stp[tid] = p.stopped[h];
+    const HypRec r = rec_now[h];
+    o_live[tid] = r.live; o_n[tid] = grp_n[h]; o_stp[tid] = p.stopped[h];
     o_tau[tid] = r.tau; o_tau_end[tid] = r.tau_end;
     o_rs[tid] = r.rs; o_re[tid] = r.re; o_last[tid] = r.last;
     o_ws[tid] = p.win_s[h]; o_we[tid] = p.win_e[h]; o_ref[tid] = r.ref;
@@ -538,9 +543,9 @@ __global__ __launch_bounds__(BLOCK) void k_select_split(Params p, int l, int cur
     if (i < NE) {
       const int j = i / Wb, r = i - j * Wb;
       const size_t o = h0 * Wb + i;
-      const int nj = p.grp_n[h0 + j];
-      const double Jv = p.grp_J[o];
-      s_tok[i] = p.grp_tok[o]; s_inc[i] = p.grp_inc[o]; s_att[i] = p.grp_att[o];
+      const int nj = grp_n[h0 + j];
+      const double Jv = grp_J[o];
+      s_tok[i] = grp_tok[o]; s_inc[i] = grp_inc[o]; s_att[i] = grp_att[o];
       s_J[i] = Jv;
       const unsigned long long b = (unsigned long long)__double_as_longlong(Jv);
       const unsigned long long k = (b >> 63) ? ~b : (b | 0x8000000000000000ull);
