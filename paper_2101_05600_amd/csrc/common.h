@@ -146,11 +146,15 @@ struct Params {
   unsigned long long* trace; // [max(U*Wb, U)][16] per-block phase time stamps (tuning builds only)
 };
 
+// natural logarithm of a normal positive number: the hardware's log2 times ln 2 (about 1.5 ulp; the
+// library's logf spends a dozen instructions more on denormal arguments and the last half ulp)
+__device__ __forceinline__ float fast_logf(float x) { return __builtin_amdgcn_logf(x) * 0.69314718055994531f; }
+
 __device__ __forceinline__ float lae(float a, float b) {
   // log(e^a + e^b); with both operands at the log0 sentinel the result stays in the log0 class
   float m = fmaxf(a, b);
   float d = -fabsf(a - b);
-  return m + __logf(1.0f + __expf(d));
+  return m + fast_logf(1.0f + __expf(d));
 }
 
 // Work-group barrier for data exchanged through LDS only.  __syncthreads() also waits for the
@@ -194,18 +198,24 @@ __device__ __forceinline__ float dpp_f(float old, float src) {
 }
 
 // all-reduce inside each row of 16 lanes (commutative op through rotations)
+// (a rotation gives every lane a source, so there is no old value to keep: the move can then be folded
+// into the instruction that consumes it)
+template <int CTRL>
+__device__ __forceinline__ float rot_f(float src) {
+  return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(src), CTRL, 0xf, 0xf, true));
+}
 __device__ __forceinline__ float row16_max(float v) {
-  v = fmaxf(v, dpp_f<0x128, 0xf>(v, v));
-  v = fmaxf(v, dpp_f<0x124, 0xf>(v, v));
-  v = fmaxf(v, dpp_f<0x122, 0xf>(v, v));
-  v = fmaxf(v, dpp_f<0x121, 0xf>(v, v));
+  v = fmaxf(v, rot_f<0x128>(v));
+  v = fmaxf(v, rot_f<0x124>(v));
+  v = fmaxf(v, rot_f<0x122>(v));
+  v = fmaxf(v, rot_f<0x121>(v));
   return v;
 }
 __device__ __forceinline__ float row16_sum(float v) {
-  v += dpp_f<0x128, 0xf>(v, v);
-  v += dpp_f<0x124, 0xf>(v, v);
-  v += dpp_f<0x122, 0xf>(v, v);
-  v += dpp_f<0x121, 0xf>(v, v);
+  v += rot_f<0x128>(v);
+  v += rot_f<0x124>(v);
+  v += rot_f<0x122>(v);
+  v += rot_f<0x121>(v);
   return v;
 }
 __device__ __forceinline__ float lane_f(float v, int lane) {

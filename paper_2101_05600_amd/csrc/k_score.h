@@ -227,7 +227,7 @@ __device__ __forceinline__ float lse_finish(Lse a) {
   if (LPC == 64) M = fmaxf(fmaxf(lane_f(M, 0), lane_f(M, 16)), fmaxf(lane_f(M, 32), lane_f(M, 48)));
   float s = row16_sum(a.s * __expf(a.m - M));
   if (LPC == 64) s = (lane_f(s, 0) + lane_f(s, 16)) + (lane_f(s, 32) + lane_f(s, 48));
-  return (M < LOG0_CLASS) ? LOG0F : M + __logf(s);
+  return (M < LOG0_CLASS) ? LOG0F : M + fast_logf(s);    // (s >= 1: the largest term contributes 1)
 }
 
 // Block-wide maximum / sum (logits mode: log-sum-exp of a whole attention row).  The per-lane

@@ -302,6 +302,11 @@ inline int __builtin_amdgcn_update_dpp(int old, int src, int ctrl, int row_mask,
   return got;
 }
 
+// the older form: no old value (a lane without a source reads 0 with bound_ctrl, else is undefined: here 0)
+inline int __builtin_amdgcn_mov_dpp(int src, int ctrl, int row_mask, int bank_mask, bool bound_ctrl) {
+  return __builtin_amdgcn_update_dpp(0, src, ctrl, row_mask, bank_mask, bound_ctrl);
+}
+
 // ---------------------------------------------------------------- scalar intrinsics
 inline int min(int a, int b) { return a < b ? a : b; }
 inline int max(int a, int b) { return a > b ? a : b; }
@@ -327,6 +332,7 @@ inline double __longlong_as_double(long long i) { double d; memcpy(&d, &i, 8); r
 inline float __expf(float x) { return expf(x); }
 inline float __logf(float x) { return logf(x); }
 inline float __builtin_amdgcn_exp2f(float x) { return exp2f(x); }
+inline float __builtin_amdgcn_logf(float x) { return log2f(x); }            // (v_log_f32 is a base-2 logarithm)
 
 // ---------------------------------------------------------------- atomics (device and LDS memory alike)
 inline int atomicAdd(int* p, int v) { return __atomic_fetch_add(p, v, __ATOMIC_SEQ_CST); }
