@@ -73,6 +73,21 @@ def test_cfg2_full_size_sampled_utterances():
     assert rep["utt_steps"] > 1500
 
 
+def test_cfg2_recipe_as_one_batch_of_512_utterances():
+    """The multi-batch launch shape of bench.py (eight cfg2 batches as ONE batch: 5120 score work-groups per
+    launch, per-utterance select kernel with eight waves per utterance): six utterances followed by the
+    oracle through every step."""
+    w = gen.workload("cfg2")
+    w["n_utt"] = 512
+    lens = gen.workload_lengths(w)
+    order = np.argsort(lens)
+    sample = sorted({int(order[0]), int(order[-1]), int(order[255]), 0, 301, 511})
+    rep, b = run_sampled("cfg2", sample, over=dict(n_utt=512))
+    print(rep, "decode steps", b.n_steps, "cells", b.cells)
+    assert rep["max_score_err"] < 1e-4 and rep["max_ctc_err"] < 1e-4
+    assert rep["utt_steps"] > 400
+
+
 def test_cfg3_one_batch_of_meeting_segments():
     """One batch of 128 Korean-meeting-like segments (V=2300), the four longest and shortest followed."""
     seg = gen.segments(2101)
