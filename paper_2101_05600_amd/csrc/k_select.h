@@ -329,7 +329,7 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
   const size_t h0 = (size_t)u * Wb;
   TRACE_POINT(p, u, 8);
 
-  // ---- round 1: every independent load ------------------------------------------------------
+  // ---- first round of loads: everything that depends on nothing --------------------------------
   if (tid < Wb) {
     const size_t h = h0 + tid;
     const HypRec r = p.rec[cur][h];
@@ -513,7 +513,7 @@ __global__ __launch_bounds__(BLOCK) void k_select_split(const HypRec* __restrict
   const bool lead = (n == 0);
   if (lead) TRACE_POINT(p, u, 8);
 
-  // ---- round 1: every independent load ------------------------------------------------------
+  // ---- first round of loads: everything that depends on nothing --------------------------------
   if (tid < Wb) {
     const size_t h = h0 + tid;
     const HypRec r = rec_now[h];
