@@ -332,17 +332,26 @@ static hipError_t allow_lds(const void* kernel, size_t bytes) {
   }
 }
 
-template <int BLOCK, int LPC, int CB, int IT>
-static hipError_t launch_score(ctcbs* h, const Params& p, const float* att, int l) {
-  hipError_t ea = allow_lds((const void*)k_score<BLOCK, LPC, CB, IT>, h->score_smem_bytes);
+template <int BLOCK, int LPC, int CB, int IT, bool E2G>
+static hipError_t launch_score_as(ctcbs* h, const Params& p, const float* att, int l) {
+  hipError_t ea = allow_lds((const void*)k_score<BLOCK, LPC, CB, IT, E2G>, h->score_smem_bytes);
   if (ea != hipSuccess) return ea;
   // attention rows that do not start on 16-byte boundaries cannot be loaded as float4: the candidate
   // selection then reads them element by element (slower, equivalent)
   const int flags = (((uintptr_t)att & 15) == 0 && p.V % 4 == 0) ? 1 : 0;
-  hipLaunchKernelGGL((k_score<BLOCK, LPC, CB, IT>), dim3(p.Wb, p.U), dim3(BLOCK), h->score_smem_bytes,
+  hipLaunchKernelGGL((k_score<BLOCK, LPC, CB, IT, E2G>), dim3(p.Wb, p.U), dim3(BLOCK), h->score_smem_bytes,
                      h->stream, (const HypRec*)p.rec[h->cur], (const UttInfo*)p.uinfo, (const uint32_t*)p.finished,
                      att, (int)p.Wb, (int)p.V, flags, l, p, h->sm, h->cur);
   return hipGetLastError();
+}
+
+// the kernel's form with the eos-run rule's work-group-wide path only where that path can be taken: the rule
+// enabled and more candidates than one wave ranks (see k_score)
+template <int BLOCK, int LPC, int CB, int IT>
+static hipError_t launch_score(ctcbs* h, const Params& p, const float* att, int l) {
+  const bool one_wave_ranks = p.K <= BLOCK && p.K <= 64 && p.V <= 65536;
+  if ((p.end_flags & 4) && !one_wave_ranks) return launch_score_as<BLOCK, LPC, CB, IT, true>(h, p, att, l);
+  return launch_score_as<BLOCK, LPC, CB, IT, false>(h, p, att, l);
 }
 
 template <int NIT>

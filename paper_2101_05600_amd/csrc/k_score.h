@@ -142,7 +142,7 @@ __device__ __forceinline__ bool select_pivot(const float4 (&v)[PIVOT_NV4], int K
 // Radix select on the order-preserving keys (10 + 10 + 10 + 2 bits) straight from the row in
 // global memory, then an ordered compaction (ascending ids).
 template <int BLOCK>
-__device__ __noinline__ void select_radix(const float* __restrict__ arow, int V, int K, int blank_id, int eos_id,
+__device__ __forceinline__ void select_radix(const float* __restrict__ arow, int V, int K, int blank_id, int eos_id,
                                           uint32_t* s_hist, uint32_t* s_scan, uint32_t* s_sel,
                                           bool use_lds, int32_t* out_lds, float* out_att_lds, int32_t* out_g) {
   const int tid = threadIdx.x;
@@ -275,7 +275,10 @@ __device__ __forceinline__ unsigned long long joint_key(double J, int tok, bool 
 // of the current buffer = p.rec[cur], p.uinfo, p.finished as words, the attention rows, p.Wb, p.V): as plain
 // leading arguments they are handed to the wave in registers when it starts (kernel-argument preload),
 // so that the record's load does not have to wait for a load of the argument block first.
-template <int BLOCK, int LPC, int CB, int IT>
+// E2G: the eos-run rule may be armed with more candidates than one wave ranks (K > 64 or ids beyond 65535): only
+// then does the kernel carry the rule's work-group-wide path (a second sum beside the first in the column pass,
+// the test across all waves), which costs registers that the common form can do without.
+template <int BLOCK, int LPC, int CB, int IT, bool E2G>
 __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(const HypRec* __restrict__ rec_now,
                                                  const UttInfo* __restrict__ uinfo, const uint32_t* __restrict__ fin_words,
                                                  const float* __restrict__ att, int Wb, int V, int flags, int l,
@@ -432,7 +435,7 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(const Hy
   // eos-run rule with few candidates: the f terms of the last R frames are kept apart (and left out of the
   // window's arrays), so that the sums below stop at frame T - R; the first wave completes them at the end
   const bool e2w = e2 && wave_rank;
-  const bool e2g = e2 && !wave_rank;                       // the rule by the whole work-group (many candidates)
+  const bool e2g = E2G && e2 && !wave_rank;                // the rule by the whole work-group (many candidates)
   for (int i = tid; i < Wp; i += BLOCK) {
     float f, fb;
     f_terms(t0 + i, f, fb);
@@ -523,9 +526,7 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(const Hy
       float inc = LOG0F, pre = LOG0F;
       {
         Lse a; a.m = LOG0F; a.s = 0.0f;
-        // (with more column loads in flight the compiler has no register to spare for the extra case: there the
-        // one-wave form takes the two-part path too; its second part is then empty)
-        if ((CB * IT <= 6) ? !e2g : !e2) {
+        if (!e2g) {
 #pragma unroll
           for (int it = 0; it < IT; ++it) {
             const int i = q + it * LPC;
@@ -588,7 +589,7 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(const Hy
   // ---------------- 4. eos-run rule, group list, outputs -----------------------------------
   // (few candidates: the first wave runs this test alone, further down, without a barrier)
   int fire = 0;
-  if (e2 && !wave_rank) {
+  if (e2g) {
     // Frame T is one of the R frames and there X_T is simply the best full prefix score of the
     // extensions, which is already known: most eligible hypotheses fail this test and skip the rest.
     if (smallk) lds_barrier(); else __syncthreads();       // s_inc / g_inc of all candidates written

@@ -39,6 +39,10 @@ CASES = {
     # more than 64 candidates per hypothesis: the group's list is ranked by the whole work-group
     "pivot_k80": (dict(n_utt=1, vocab=1024, beam=2, cand_k=80, win_m1=-1, win_m2=-1, end_flags=3,
                        max_len_ratio=0.3), [12]),
+    # eos-run rule armed with more candidates than one wave ranks: the kernel form that carries the rule's
+    # work-group-wide path (second sum in the column pass, test across all waves)
+    "k80_eos_run": (dict(n_utt=2, vocab=1024, beam=2, cand_k=80, win_m1=6, win_m2=6, end_flags=7, eos_run=3,
+                         max_len_ratio=0.4), [14, 9]),
     # a vocabulary beyond 65535 whose attention rows are constant: the radix selection meets more equal keys
     # than 16 bits count, and the K smallest ids must come out
     "radix_wide_ties": (dict(n_utt=1, vocab=66000, beam=1, cand_k=3, win_m1=-1, win_m2=-1, end_flags=3,

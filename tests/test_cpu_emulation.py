@@ -78,7 +78,7 @@ def runs(tmp_path_factory):
     plan = {
         "asan": (asan, ASAN_ENV, dict(sanitize=True),
                  ["windowed", "batch_window", "all_candidates", "all_candidates_few_ids", "logits_odd_vocab",
-                  "pivot", "pivot_k80", "static_step", "radix_wide_ties", "wide_window_eos_run"]),
+                  "pivot", "pivot_k80", "static_step", "radix_wide_ties", "wide_window_eos_run", "k80_eos_run"]),
         # the first steps of a fixed subset of the random configurations that tests/test_gpu_random_configs.py
         # decodes on the GPU (same table, tests/random_cases.py), device memory starting out as garbage
         "asan_random": (asan, ASAN_ENV, dict(sanitize=True), [f"random:{a}:{b}:{c}" for a, b, c in CPU_SUBSET]),
@@ -111,7 +111,7 @@ def test_kernels_under_address_and_ub_sanitizers(runs):
     r, out = _result(runs, "asan")
     assert r.returncode == 0, out[-4000:]
     assert "ERROR: AddressSanitizer" not in out and "runtime error:" not in out, out[-4000:]
-    assert out.count("emu ok") == 10, out[-2000:]
+    assert out.count("emu ok") == 11, out[-2000:]
 
 
 def test_random_configurations_first_steps_under_address_sanitizer(runs):

@@ -35,12 +35,14 @@ def test_cfg0_full_vocabulary_single_utterance():
     assert res["cells"] == int(res["oracle_cells"])
 
 
-@pytest.mark.parametrize("variant", ["topk", "topk_window_e2", "fullv_window", "beam1", "wide_beam"])
+@pytest.mark.parametrize("variant", ["topk", "topk_window_e2", "topk_k80_window_e2", "fullv_window", "beam1", "wide_beam"])
 def test_small_batches_ragged(variant):
     base = dict(n_utt=5, t_lo=37, t_hi=211, vocab=700, beam=6, cand_k=24, win_m1=-1, win_m2=-1,
                 end_flags=3)
     if variant == "topk_window_e2":
         base.update(win_m1=12, win_m2=17, end_flags=7, eos_run=6)
+    elif variant == "topk_k80_window_e2":              # more candidates than one wave ranks, eos-run rule armed
+        base.update(cand_k=80, win_m1=12, win_m2=17, end_flags=7, eos_run=6)
     elif variant == "fullv_window":
         base.update(vocab=90, cand_k=0, win_m1=9, win_m2=30, end_flags=7, beam=5)
     elif variant == "beam1":
