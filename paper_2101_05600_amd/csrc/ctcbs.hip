@@ -44,6 +44,7 @@ struct ctcbs {
   int32_t known_finished;
   size_t score_smem_bytes;
   int score_block, score_lpc, select_block;
+  bool select_fpl2;            // the select kernels' form with the two-frames-per-lane recurrence only
   bool score_wide;
   int dense_nit, dense_nch;   // all-candidates score kernel: float4 per lane and column (0: not used), chunks per utterance
   size_t dense_smem_bytes;
@@ -284,6 +285,9 @@ static int create_impl(ctcbs* h, const float* d_ctc_logp, const int32_t* h_lens)
     h->dense_nch = nch < 1 ? 1 : (nch > most ? most : nch);
   }
   if (off > 160 * 1024) return CTCBS_EINVAL;
+  // per-hypothesis windows whose margins keep them within 128 frames (but for a hypothesis whose two time
+  // indices lie far apart): the select kernels then carry the two-frames-per-lane recurrence only
+  h->select_fpl2 = windowed && !c.win_union && (c.win_m1 + c.win_m2 + 1 + 3) <= 128;
   int nw = Wb < 16 ? Wb : 16;
   h->select_block = 64 * (nw <= 4 ? 4 : (nw <= 8 ? 8 : 16));
   // One wave for the ended set plus one per new hypothesis is the shape that finishes an utterance soonest.
@@ -332,25 +336,24 @@ static hipError_t allow_lds(const void* kernel, size_t bytes) {
   }
 }
 
-template <int BLOCK, int LPC, int CB, int IT, bool E2G>
+template <int BLOCK, int LPC, int CB, int IT, bool BIGK>
 static hipError_t launch_score_as(ctcbs* h, const Params& p, const float* att, int l) {
-  hipError_t ea = allow_lds((const void*)k_score<BLOCK, LPC, CB, IT, E2G>, h->score_smem_bytes);
+  hipError_t ea = allow_lds((const void*)k_score<BLOCK, LPC, CB, IT, BIGK>, h->score_smem_bytes);
   if (ea != hipSuccess) return ea;
   // attention rows that do not start on 16-byte boundaries cannot be loaded as float4: the candidate
   // selection then reads them element by element (slower, equivalent)
   const int flags = (((uintptr_t)att & 15) == 0 && p.V % 4 == 0) ? 1 : 0;
-  hipLaunchKernelGGL((k_score<BLOCK, LPC, CB, IT, E2G>), dim3(p.Wb, p.U), dim3(BLOCK), h->score_smem_bytes,
+  hipLaunchKernelGGL((k_score<BLOCK, LPC, CB, IT, BIGK>), dim3(p.Wb, p.U), dim3(BLOCK), h->score_smem_bytes,
                      h->stream, (const HypRec*)p.rec[h->cur], (const UttInfo*)p.uinfo, (const uint32_t*)p.finished,
                      att, (int)p.Wb, (int)p.V, flags, l, p, h->sm, h->cur);
   return hipGetLastError();
 }
 
-// the kernel's form with the eos-run rule's work-group-wide path only where that path can be taken: the rule
-// enabled and more candidates than one wave ranks (see k_score)
+// the kernel's form with the paths for many candidates only where they can be taken (see k_score)
 template <int BLOCK, int LPC, int CB, int IT>
 static hipError_t launch_score(ctcbs* h, const Params& p, const float* att, int l) {
   const bool one_wave_ranks = p.K <= BLOCK && p.K <= 64 && p.V <= 65536;
-  if ((p.end_flags & 4) && !one_wave_ranks) return launch_score_as<BLOCK, LPC, CB, IT, true>(h, p, att, l);
+  if (!one_wave_ranks) return launch_score_as<BLOCK, LPC, CB, IT, true>(h, p, att, l);
   return launch_score_as<BLOCK, LPC, CB, IT, false>(h, p, att, l);
 }
 
@@ -407,13 +410,24 @@ static int step_impl(ctcbs_t* h, const Params& p, const float* d_att_logp, ctcbs
   const bool split = !p.win_union && p.U * p.Wb <= 2048;
   const size_t split_lds = (size_t)28 * p.Wb * p.Wb + 64;
   if (split) {
-    hipLaunchKernelGGL((k_select_split<256>), dim3(p.U * p.Wb), dim3(256), split_lds, h->stream,
-                       (const HypRec*)p.rec[h->cur], p.utt, (const int32_t*)p.grp_n, (const double*)p.grp_J,
-                       (const int32_t*)p.grp_tok, (const float*)p.grp_inc, (const float*)p.grp_att, (int)p.Wb, l, p, h->cur);
-  } else switch (h->select_block) {
-    case 256: hipLaunchKernelGGL((k_select<256>), dim3(p.U), dim3(256), 0, h->stream, p, l, h->cur); break;
-    case 512: hipLaunchKernelGGL((k_select<512>), dim3(p.U), dim3(512), 0, h->stream, p, l, h->cur); break;
-    default: hipLaunchKernelGGL((k_select<1024>), dim3(p.U), dim3(1024), 0, h->stream, p, l, h->cur); break;
+    if (h->select_fpl2)
+      hipLaunchKernelGGL((k_select_split<256, 2>), dim3(p.U * p.Wb), dim3(256), split_lds, h->stream,
+                         (const HypRec*)p.rec[h->cur], p.utt, (const int32_t*)p.grp_n, (const double*)p.grp_J,
+                         (const int32_t*)p.grp_tok, (const float*)p.grp_inc, (const float*)p.grp_att, (int)p.Wb, l, p, h->cur);
+    else
+      hipLaunchKernelGGL((k_select_split<256, 8>), dim3(p.U * p.Wb), dim3(256), split_lds, h->stream,
+                         (const HypRec*)p.rec[h->cur], p.utt, (const int32_t*)p.grp_n, (const double*)p.grp_J,
+                         (const int32_t*)p.grp_tok, (const float*)p.grp_inc, (const float*)p.grp_att, (int)p.Wb, l, p, h->cur);
+  } else {
+    const int NE = p.Wb * p.Wb;
+    const size_t sel_lds = (size_t)16 * ((NE + 9) & ~1) + (size_t)32 * NE;
+#define CTCBS_SELECT(BS, F) hipLaunchKernelGGL((k_select<BS, F>), dim3(p.U), dim3(BS), sel_lds, h->stream, p, l, h->cur)
+    switch (h->select_block) {
+      case 256: if (h->select_fpl2) CTCBS_SELECT(256, 2); else CTCBS_SELECT(256, 8); break;
+      case 512: if (h->select_fpl2) CTCBS_SELECT(512, 2); else CTCBS_SELECT(512, 8); break;
+      default: if (h->select_fpl2) CTCBS_SELECT(1024, 2); else CTCBS_SELECT(1024, 8); break;
+    }
+#undef CTCBS_SELECT
   }
   HIPCHK(hipGetLastError());
   if (ev) HIPCHK(hipEventRecord(ev[2], h->stream));

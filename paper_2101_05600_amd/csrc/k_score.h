@@ -275,10 +275,12 @@ __device__ __forceinline__ unsigned long long joint_key(double J, int tok, bool 
 // of the current buffer = p.rec[cur], p.uinfo, p.finished as words, the attention rows, p.Wb, p.V): as plain
 // leading arguments they are handed to the wave in registers when it starts (kernel-argument preload),
 // so that the record's load does not have to wait for a load of the argument block first.
-// E2G: the eos-run rule may be armed with more candidates than one wave ranks (K > 64 or ids beyond 65535): only
-// then does the kernel carry the rule's work-group-wide path (a second sum beside the first in the column pass,
-// the test across all waves), which costs registers that the common form can do without.
-template <int BLOCK, int LPC, int CB, int IT, bool E2G>
+// BIGK: more candidates per hypothesis than one wave ranks (K > 64, or ids beyond 65535).  Only that form of the
+// kernel carries the paths for it: candidate arrays in global memory when K exceeds the work-group, the exact
+// ranking by the whole work-group, the eos-run rule's work-group-wide path (a second sum beside the first in
+// the column pass, the test across all waves).  They cost registers that the common form does without (69
+// against 77-89, i.e. seven work-groups per compute unit against five or six).
+template <int BLOCK, int LPC, int CB, int IT, bool BIGK>
 __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(const HypRec* __restrict__ rec_now,
                                                  const UttInfo* __restrict__ uinfo, const uint32_t* __restrict__ fin_words,
                                                  const float* __restrict__ att, int Wb, int V, int flags, int l,
@@ -305,7 +307,7 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(const Hy
   const uint32_t fin_word = fin_words[u >> 2];
   TRACE_DECL;
   const int K = p.K;
-  const bool smallk = (K <= BLOCK);
+  const bool smallk = !BIGK || (K <= BLOCK);
 
   // ---------------- the attention row -----------------------------------------------------------
   // As soon as the record says that the slot holds a hypothesis its row is fetched, all loads in
@@ -431,11 +433,11 @@ __global__ __launch_bounds__(BLOCK, (CB * IT > 8 ? 4 : 5)) void k_score(const Hy
   const int R = p.eos_run;
   const bool e2 = (p.end_flags & 4) && R > 0 && T >= R && W > 0 && e == T && re == T &&
                   max(s, rs) <= T - R + 1;
-  const bool wave_rank = smallk && K <= 64 && V <= 65536;  // the group's list is ranked by one wave on 64-bit keys
+  const bool wave_rank = !BIGK || (smallk && K <= 64 && V <= 65536);  // the group's list is ranked by one wave on 64-bit keys
   // eos-run rule with few candidates: the f terms of the last R frames are kept apart (and left out of the
   // window's arrays), so that the sums below stop at frame T - R; the first wave completes them at the end
   const bool e2w = e2 && wave_rank;
-  const bool e2g = E2G && e2 && !wave_rank;                // the rule by the whole work-group (many candidates)
+  const bool e2g = BIGK && e2 && !wave_rank;               // the rule by the whole work-group (many candidates)
   for (int i = tid; i < Wp; i += BLOCK) {
     float f, fb;
     f_terms(t0 + i, f, fb);

@@ -172,11 +172,15 @@ __device__ __forceinline__ void wave_survivor_fpl(const Params& p, int u, int n,
 }
 
 // windows of up to 128 frames: two frames per lane, one pass; up to 256: four per lane (a pass costs
-// about 1.4 times as much and covers twice as many frames); longer ones: eight per lane
+// about 1.4 times as much and covers twice as many frames); longer ones: eight per lane.
+// FPLMAX = 2: the kernel carries the two-frames form only (wider windows take several passes of it).  The
+// host asks for that when the window margins keep windows within 128 frames but for rare exceptions: the
+// forms with more frames per lane are what sets the kernel's register count (97 against 58).
+template <int FPLMAX>
 __device__ __forceinline__ void wave_survivor(const Params& p, int u, int n, int cur, const SurvivorIn& in,
                                               int& arg_n, int& arg_b, float& delta_out, double& bref_out) {
   const int W = in.en - in.s + 1;
-  if (W <= 128) wave_survivor_fpl<2>(p, u, n, cur, in, arg_n, arg_b, delta_out, bref_out);
+  if (FPLMAX == 2 || W <= 128) wave_survivor_fpl<2>(p, u, n, cur, in, arg_n, arg_b, delta_out, bref_out);
   else if (W <= 256) wave_survivor_fpl<4>(p, u, n, cur, in, arg_n, arg_b, delta_out, bref_out);
   else wave_survivor_fpl<8>(p, u, n, cur, in, arg_n, arg_b, delta_out, bref_out);
 }
@@ -299,17 +303,23 @@ __device__ __forceinline__ bool wave_ended_set(const Params& p, int u, int l, in
   return fin;
 }
 
-template <int BLOCK>
+// Dynamic LDS: 16 * ((Wb * Wb + 9) & ~1) + 32 * Wb * Wb bytes (the list entries and the packed contenders).
+template <int BLOCK, int FPLMAX>
 __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
   constexpr int NW = BLOCK / 64;
-  constexpr int MAXE = MAX_BEAM * MAX_BEAM;
-  __shared__ double s_J[MAXE];
-  __shared__ __align__(16) unsigned long long s_key[MAXE + 8];
-  __shared__ int s_par[MAXE], s_ci[MAXE], s_tok[MAXE];
-  __shared__ float s_inc[MAXE], s_att[MAXE];
+  extern __shared__ __align__(16) unsigned char sel_smem[];
+  const int NE_ = p.Wb * p.Wb;
+  const int NK_ = (NE_ + 9) & ~1;                                     // NE + 8 keys, an even count: both key arrays on 16-byte boundaries
+  unsigned long long* s_key = (unsigned long long*)sel_smem;          // [NE + 8]
+  unsigned long long* s_ck = s_key + NK_;                             // [NE + 8] keys of the entries that can reach the new beam
+  double* s_J = (double*)(s_ck + NK_);                                // [NE]
+  int* s_par = (int*)(s_J + NE_);                                     // [NE] each
+  int* s_ci = s_par + NE_;
+  int* s_tok = s_ci + NE_;
+  int* s_cidx = s_tok + NE_;
+  float* s_inc = (float*)(s_cidx + NE_);
+  float* s_att = s_inc + NE_;
   __shared__ int s_sel[MAX_BEAM];          // entry index of the new beam's slot n
-  __shared__ __align__(16) unsigned long long s_ck[MAXE + 8];   // keys of the entries that can reach the new beam
-  __shared__ int s_cidx[MAXE];
   __shared__ int s_cnt[2];
   __shared__ unsigned long long s_min;
   // old slots' records
@@ -429,7 +439,7 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
     int arg_n, arg_b;
     float delta;
     double bref;
-    wave_survivor(p, u, n, cur, in, arg_n, arg_b, delta, bref);
+    wave_survivor<FPLMAX>(p, u, n, cur, in, arg_n, arg_b, delta, bref);
     if (lane == 0) {
       p.out_tau[h0 + n] = arg_n; p.out_tau_end[h0 + n] = arg_b;
       p.trie_tau[trie_l + n] = arg_n;
@@ -485,7 +495,7 @@ __global__ __launch_bounds__(BLOCK) void k_select(Params p, int l, int cur) {
 // The arguments in front of the parameter block are what the first round of loads needs (p.rec[cur], p.utt,
 // p.grp_n and the list arrays, p.Wb): plain leading arguments reach the wave in registers when it starts
 // (kernel-argument preload), so that those loads do not wait for a load of the argument block first.
-template <int BLOCK>
+template <int BLOCK, int FPLMAX>
 __global__ __launch_bounds__(BLOCK) void k_select_split(const HypRec* __restrict__ rec_now, UttState* __restrict__ utt,
                                                         const int32_t* __restrict__ grp_n, const double* __restrict__ grp_J,
                                                         const int32_t* __restrict__ grp_tok, const float* __restrict__ grp_inc,
@@ -599,7 +609,7 @@ __global__ __launch_bounds__(BLOCK) void k_select_split(const HypRec* __restrict
       int arg_n, arg_b;
       float delta;
       double bref;
-      wave_survivor(p, u, n, cur, in, arg_n, arg_b, delta, bref);
+      wave_survivor<FPLMAX>(p, u, n, cur, in, arg_n, arg_b, delta, bref);
       if (lane == 0) {
         p.out_tau[h] = arg_n; p.out_tau_end[h] = arg_b;
         p.trie_tau[trie_l + n] = arg_n;
